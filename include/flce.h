@@ -1,0 +1,142 @@
+/*
+ * flce.h - C ABI of the MI355X (gfx950) fused linear cross-entropy library.
+ *
+ * One call computes, for hidden states X[BT x H], an output-projection weight
+ * W[V x H] and integer targets[BT],
+ *
+ *     logits   z_i = W x_i                                  (never stored whole)
+ *     loss       L = -(1/N) sum_{i valid} log softmax(z_i)[t_i]
+ *     dX_i         = W^T g_i,      dW = sum_i g_i x_i^T,
+ *     g_i          = (softmax(z_i) - onehot(t_i)) / N  for valid i, 0 otherwise,
+ *
+ * where a row is valid when t_i != ignore_index and N is the number of valid
+ * rows.  This is the paper's FusedLinearCrossEntropy (section 3.2, FLCE
+ * paragraph and Eq. FLCE-backward) on top of its CrossEntropy kernel (CE
+ * paragraph, Eq. CE-forward / CE-backward): rows are processed in chunks, each
+ * chunk's logits are turned into their gradient in place, and only one chunk
+ * of logits exists at any time.  Deviation from the paper's remark on mean
+ * reduction: every gradient is divided by the global N (counted on the device
+ * before the chunk loop), so the result does not depend on the chunk size.
+ *
+ * Conventions
+ *  - All matrices are dense row-major; X, W, dX, dW, loss, targets are DEVICE
+ *    pointers owned by the caller.  X, W, dX, dW must be 16-byte aligned,
+ *    targets 8-byte, loss 4-byte.  Inputs are not modified.  dX, dW and loss
+ *    are fully overwritten (rows of dX whose target is ignored become 0).
+ *  - dtype selects the storage type of X, W, dX, dW (flce_dtype).  Products
+ *    accumulate in fp32; the reduction math is fp32; loss is fp32.
+ *  - Targets must lie in [0, V) or equal ignore_index; anything else is a
+ *    precondition violation (not detected: checking would need a host sync).
+ *  - N == 0 gives loss = 0, dX = 0, dW = 0.
+ *  - The upstream gradient of the loss is 1.  There is no bias term.
+ *  - Every call is asynchronous: all work is enqueued on `stream` (a
+ *    hipStream_t, NULL = the default stream) and the function returns without
+ *    synchronising.  Argument errors are found on the host before anything is
+ *    launched.  Functions return an flce_status and never throw or abort.
+ *  - Scratch memory ("workspace") lives on the device.  Either the caller
+ *    lends a buffer with flce_set_workspace, or the library allocates one per
+ *    device on first use and keeps it (growing it if a later call needs more;
+ *    growing synchronises the device).  Calls that overlap in time on the same
+ *    device share the workspace and therefore race: serialise them on one
+ *    stream.
+ */
+#ifndef FLCE_H
+#define FLCE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#if defined(__GNUC__)
+#define FLCE_API __attribute__((visibility("default")))
+#else
+#define FLCE_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { FLCE_F32 = 0, FLCE_BF16 = 1 } flce_dtype;
+
+typedef enum {
+    FLCE_OK = 0,
+    FLCE_ERR_NULL = 1,      /* a required pointer is NULL                     */
+    FLCE_ERR_SHAPE = 2,     /* BT, H or V is not positive / too large         */
+    FLCE_ERR_DTYPE = 3,     /* dtype is not an flce_dtype                     */
+    FLCE_ERR_ALIGN = 4,     /* a pointer misses its alignment                 */
+    FLCE_ERR_WORKSPACE = 5, /* lent workspace too small, or allocation failed */
+    FLCE_ERR_HIP = 6,       /* a HIP runtime call or kernel launch failed     */
+    FLCE_ERR_ARG = 7        /* any other invalid argument                     */
+} flce_status;
+
+/* Flags for flce_fwd_bwd_ex: skip one of the two gradients (a frozen backbone
+ * needs no dX, a frozen head needs no dW).  The skipped output may be NULL. */
+enum { FLCE_SKIP_DX = 1, FLCE_SKIP_DW = 2 };
+
+/*
+ * The whole hot path: loss, dX and dW (paper section 3.2, FLCE paragraph).
+ *   X        device, [BT x H] dtype          in
+ *   W        device, [V x H]  dtype          in
+ *   targets  device, [BT] int64              in
+ *   loss     device, 1 float                 out (mean over valid rows)
+ *   dX       device, [BT x H] dtype          out
+ *   dW       device, [V x H]  dtype          out
+ *   stream   hipStream_t
+ */
+FLCE_API int flce_fwd_bwd(const void* X, const void* W, const int64_t* targets, int64_t BT, int64_t H,
+                 int64_t V, int64_t ignore_index, int dtype, float* loss, void* dX, void* dW,
+                 void* stream);
+
+/* Same, with FLCE_SKIP_* flags (paper section 4.2, Medusa paragraph: extra
+ * heads trained on a frozen backbone need no hidden-state gradient). */
+FLCE_API int flce_fwd_bwd_ex(const void* X, const void* W, const int64_t* targets, int64_t BT, int64_t H,
+                    int64_t V, int64_t ignore_index, int dtype, float* loss, void* dX, void* dW,
+                    unsigned flags, void* stream);
+
+/*
+ * Stand-alone cross entropy on given logits (paper section 3.2, CE paragraph):
+ * Z[BT x V] (device, dtype, row stride ldz elements, ldz >= V) is replaced in
+ * place by dL/dZ; loss receives the mean over valid rows.  Needs no workspace
+ * beyond a few kilobytes.
+ */
+FLCE_API int flce_cross_entropy_inplace(void* Z, const int64_t* targets, int64_t BT, int64_t V,
+                               int64_t ldz, int64_t ignore_index, int dtype, float* loss,
+                               void* stream);
+
+/* Bytes of device scratch flce_fwd_bwd uses for this problem.  For fixed H, V
+ * and dtype it does not grow with BT once BT exceeds one chunk:
+ * flce_workspace_bytes(BT, ...) <= flce_workspace_bytes_max(...). */
+FLCE_API size_t flce_workspace_bytes(int64_t BT, int64_t H, int64_t V, int dtype);
+FLCE_API size_t flce_workspace_bytes_max(int64_t H, int64_t V, int dtype);
+
+/* Lend a device buffer (256-byte aligned) as workspace for the current device;
+ * ws == NULL returns to library-owned allocation.  The library never frees a
+ * lent buffer. */
+FLCE_API int flce_set_workspace(void* ws, size_t bytes);
+
+/* Free the library-owned workspace of the current device (synchronises). */
+FLCE_API int flce_release_workspace(void);
+
+/* Chunk scheduler (paper section 3.2, FLCE paragraph: chunked logits bound the
+ * memory).  The logits chunk [C x V] is sized to fit this many bytes; default
+ * 1 GiB.  Returns FLCE_ERR_ARG for 0. */
+FLCE_API int flce_set_logits_budget_bytes(size_t bytes);
+FLCE_API size_t flce_get_logits_budget_bytes(void);
+
+/* Rows per chunk C and number of chunks the scheduler picks (host only). */
+FLCE_API int64_t flce_chunk_rows(int64_t BT, int64_t H, int64_t V, int dtype);
+FLCE_API int64_t flce_num_chunks(int64_t BT, int64_t H, int64_t V, int dtype);
+
+/* The paper's own chunk-size rule, 2^ceil(log2(ceil(BT / ceil(V/H)))), for
+ * reference and reporting; the scheduler above does not use it. */
+FLCE_API int64_t flce_paper_chunk_rows(int64_t BT, int64_t H, int64_t V);
+
+/* Bytes of the full logits tensor BT x V that is never materialised. */
+FLCE_API size_t flce_full_logits_bytes(int64_t BT, int64_t V, int dtype);
+
+FLCE_API const char* flce_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLCE_H */

@@ -1,0 +1,187 @@
+"""Thin Python binding of the C ABI in include/flce.h: argument marshalling only.
+
+Every step of the path (projection, cross entropy, both gradients, the chunk
+loop) runs inside libflce.so; PyTorch is used for device memory and streams.
+There is no fallback: if the library is missing or a call fails, this raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch  # imported before the library so both share one HIP runtime
+
+from . import _build
+
+FLCE_F32, FLCE_BF16 = 0, 1
+SKIP_DX, SKIP_DW = 1, 2
+_DTYPES = {torch.float32: FLCE_F32, torch.bfloat16: FLCE_BF16}
+
+_lib = None
+
+
+class FlceError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: status {status} ({status_string(status)})")
+        self.status = status
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libflce.so (building it first only if no built library exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB_PATH):
+            _build.build()
+        L = ctypes.CDLL(_build.LIB_PATH)
+        p, i64, sz, ci, u = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t, ctypes.c_int, ctypes.c_uint
+        sigs = {
+            "flce_fwd_bwd": ([p, p, p, i64, i64, i64, i64, ci, p, p, p, p], ci),
+            "flce_fwd_bwd_ex": ([p, p, p, i64, i64, i64, i64, ci, p, p, p, u, p], ci),
+            "flce_cross_entropy_inplace": ([p, p, i64, i64, i64, i64, ci, p, p], ci),
+            "flce_workspace_bytes": ([i64, i64, i64, ci], sz),
+            "flce_workspace_bytes_max": ([i64, i64, ci], sz),
+            "flce_set_workspace": ([p, sz], ci),
+            "flce_release_workspace": ([], ci),
+            "flce_set_logits_budget_bytes": ([sz], ci),
+            "flce_get_logits_budget_bytes": ([], sz),
+            "flce_chunk_rows": ([i64, i64, i64, ci], i64),
+            "flce_num_chunks": ([i64, i64, i64, ci], i64),
+            "flce_paper_chunk_rows": ([i64, i64, i64], i64),
+            "flce_full_logits_bytes": ([i64, i64, ci], sz),
+            "flce_status_string": ([ci], ctypes.c_char_p),
+        }
+        for name, (args, res) in sigs.items():
+            fn = getattr(L, name)
+            fn.argtypes, fn.restype = args, res
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().flce_status_string(int(status)).decode()
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        raise FlceError(status, what)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    try:
+        return _DTYPES[t.dtype]
+    except KeyError:
+        raise TypeError(f"unsupported dtype {t.dtype}; use float32 or bfloat16") from None
+
+
+def _dev_ptr(t: torch.Tensor | None, name: str) -> int | None:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous (dense row-major)")
+    return t.data_ptr()
+
+
+def _stream_handle(stream) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def flce_fwd_bwd(X, W, targets, ignore_index=-100, loss=None, dX=None, dW=None, flags=0,
+                 stream=None):
+    """loss, dX, dW of mean cross_entropy(X @ W.T, targets) on the GPU, chunked.
+
+    X [BT, H], W [V, H] (float32 or bfloat16, same dtype), targets [BT] int64,
+    all contiguous CUDA tensors.  Outputs are allocated when not passed.
+    Asynchronous on `stream` (default: torch's current stream).
+    """
+    code = _dtype_code(X)
+    if W.dtype != X.dtype:
+        raise TypeError("X and W must have the same dtype")
+    if X.dim() != 2 or W.dim() != 2 or X.shape[1] != W.shape[1] or targets.shape != (X.shape[0],):
+        raise ValueError("expected X [BT, H], W [V, H], targets [BT]")
+    if targets.dtype != torch.int64:
+        raise TypeError("targets must be int64")
+    BT, H = X.shape
+    V = W.shape[0]
+    if loss is None:
+        loss = torch.empty((), dtype=torch.float32, device=X.device)
+    if dX is None and not (flags & SKIP_DX):
+        dX = torch.empty_like(X)
+    if dW is None and not (flags & SKIP_DW):
+        dW = torch.empty_like(W)
+    for name, t, ref in (("dX", dX, X), ("dW", dW, W)):
+        if t is not None and (t.shape != ref.shape or t.dtype != ref.dtype):
+            raise ValueError(f"{name} must match its input in shape and dtype")
+    with torch.cuda.device(X.device):
+        st = lib().flce_fwd_bwd_ex(_dev_ptr(X, "X"), _dev_ptr(W, "W"), _dev_ptr(targets, "targets"),
+                                   BT, H, V, int(ignore_index), code, _dev_ptr(loss, "loss"),
+                                   _dev_ptr(dX, "dX"), _dev_ptr(dW, "dW"), int(flags),
+                                   _stream_handle(stream))
+    _check(st, "flce_fwd_bwd")
+    return loss, dX, dW
+
+
+def flce_cross_entropy_inplace(Z, targets, ignore_index=-100, loss=None, stream=None):
+    """Replaces logits Z [BT, V] (row stride Z.stride(0)) by dL/dZ; returns the mean loss."""
+    code = _dtype_code(Z)
+    if Z.dim() != 2 or Z.stride(1) != 1 or targets.shape != (Z.shape[0],):
+        raise ValueError("expected Z [BT, V] with unit column stride, targets [BT]")
+    if targets.dtype != torch.int64 or not Z.is_cuda:
+        raise TypeError("targets must be int64 and Z on the GPU")
+    BT, V = Z.shape
+    if loss is None:
+        loss = torch.empty((), dtype=torch.float32, device=Z.device)
+    with torch.cuda.device(Z.device):
+        st = lib().flce_cross_entropy_inplace(Z.data_ptr(), _dev_ptr(targets, "targets"), BT, V,
+                                              Z.stride(0) if BT > 1 else max(V, Z.stride(0)),
+                                              int(ignore_index), code, _dev_ptr(loss, "loss"),
+                                              _stream_handle(stream))
+    _check(st, "flce_cross_entropy_inplace")
+    return loss
+
+
+def flce_workspace_bytes(BT, H, V, dtype) -> int:
+    return int(lib().flce_workspace_bytes(BT, H, V, _DTYPES.get(dtype, dtype)))
+
+
+def flce_workspace_bytes_max(H, V, dtype) -> int:
+    return int(lib().flce_workspace_bytes_max(H, V, _DTYPES.get(dtype, dtype)))
+
+
+def flce_set_workspace(ws: torch.Tensor | None):
+    if ws is None:
+        _check(lib().flce_set_workspace(None, 0), "flce_set_workspace")
+    else:
+        with torch.cuda.device(ws.device):
+            _check(lib().flce_set_workspace(ws.data_ptr(), ws.numel() * ws.element_size()),
+                   "flce_set_workspace")
+
+
+def flce_release_workspace():
+    _check(lib().flce_release_workspace(), "flce_release_workspace")
+
+
+def flce_set_logits_budget_bytes(n: int):
+    _check(lib().flce_set_logits_budget_bytes(int(n)), "flce_set_logits_budget_bytes")
+
+
+def flce_get_logits_budget_bytes() -> int:
+    return int(lib().flce_get_logits_budget_bytes())
+
+
+def flce_chunk_rows(BT, H, V, dtype) -> int:
+    return int(lib().flce_chunk_rows(BT, H, V, _DTYPES.get(dtype, dtype)))
+
+
+def flce_num_chunks(BT, H, V, dtype) -> int:
+    return int(lib().flce_num_chunks(BT, H, V, _DTYPES.get(dtype, dtype)))
+
+
+def flce_paper_chunk_rows(BT, H, V) -> int:
+    return int(lib().flce_paper_chunk_rows(BT, H, V))
+
+
+def flce_full_logits_bytes(BT, V, dtype) -> int:
+    return int(lib().flce_full_logits_bytes(BT, V, _DTYPES.get(dtype, dtype)))

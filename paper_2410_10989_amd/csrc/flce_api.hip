@@ -1,0 +1,334 @@
+// C ABI of the fused linear cross-entropy library for gfx950: argument checks,
+// chunk loop, workspace handling, kernel launches.  Declarations and the
+// meaning of every argument are in include/flce.h.
+#include <hip/hip_runtime.h>
+#include <mutex>
+
+#include "../../include/flce.h"
+#include "flce_device.h"
+#include "gemm_generic.h"
+#include "misc_kernels.h"
+#include "rowreduce.h"
+#include "scheduler.h"
+
+using namespace flce;
+
+namespace {
+
+constexpr int MAX_DEVICES = 64;
+constexpr int64_t MAX_DIM = (int64_t)1 << 30;      // per-dimension limit, keeps int tile math safe
+constexpr int64_t CE_ROWS_PER_LAUNCH = 65536;
+
+struct DeviceWorkspace {
+    void* lent = nullptr;
+    size_t lent_bytes = 0;
+    void* own = nullptr;
+    size_t own_bytes = 0;
+};
+
+std::mutex g_mutex;
+DeviceWorkspace g_ws[MAX_DEVICES];
+size_t g_budget = (size_t)1 << 30;
+
+#define HIP_TRY(expr)                          \
+    do {                                       \
+        if ((expr) != hipSuccess) {            \
+            (void)hipGetLastError();           \
+            return FLCE_ERR_HIP;               \
+        }                                      \
+    } while (0)
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int acquire_workspace(size_t need, char** out) {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return FLCE_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceWorkspace& w = g_ws[dev];
+    if (w.lent) {
+        if (w.lent_bytes < need) return FLCE_ERR_WORKSPACE;
+        *out = static_cast<char*>(w.lent);
+        return FLCE_OK;
+    }
+    if (w.own_bytes < need) {
+        if (w.own) {
+            HIP_TRY(hipDeviceSynchronize());
+            HIP_TRY(hipFree(w.own));
+            w.own = nullptr;
+            w.own_bytes = 0;
+        }
+        if (hipMalloc(&w.own, need) != hipSuccess) {
+            (void)hipGetLastError();
+            w.own = nullptr;
+            return FLCE_ERR_WORKSPACE;
+        }
+        w.own_bytes = need;
+    }
+    *out = static_cast<char*>(w.own);
+    return FLCE_OK;
+}
+
+// C[M x N] (+)= A[M x K] * B[N x K]^T on the generic guarded kernel.
+template <typename T, typename OutT>
+int launch_gemm_generic(const T* A, int64_t lda, const T* B, int64_t ldb, OutT* C, int64_t ldc,
+                        int64_t M, int64_t N, int64_t K, bool accum, hipStream_t s) {
+    if (M <= 0 || N <= 0) return FLCE_OK;
+    constexpr int VEC = GGTraits<T>::VEC;
+    const bool al = (K % VEC == 0) && (lda % VEC == 0) && (ldb % VEC == 0) && aligned(A, 16) &&
+                    aligned(B, 16);
+    dim3 grid((unsigned)((N + GG_BN - 1) / GG_BN), (unsigned)((M + GG_BM - 1) / GG_BM));
+    dim3 block(GG_THREADS);
+#define GG_LAUNCH(AL, AC)                                                                       \
+    hipLaunchKernelGGL((gemm_nt_generic<T, OutT, AL, AC>), grid, block, 0, s, A, lda, B, ldb, C, \
+                       ldc, (int)M, (int)N, (int)K)
+    if (al) {
+        if (accum) GG_LAUNCH(true, true); else GG_LAUNCH(true, false);
+    } else {
+        if (accum) GG_LAUNCH(false, true); else GG_LAUNCH(false, false);
+    }
+#undef GG_LAUNCH
+    HIP_TRY(hipGetLastError());
+    return FLCE_OK;
+}
+
+template <typename T>
+int launch_transpose(const T* in, int64_t ldin, T* out, int64_t ldout, int64_t R, int64_t Cc,
+                     hipStream_t s) {
+    if (R <= 0 || Cc <= 0) return FLCE_OK;
+    dim3 grid((unsigned)((Cc + 63) / 64), (unsigned)((R + 63) / 64));
+    hipLaunchKernelGGL((transpose_kernel<T>), grid, dim3(256), 0, s, in, ldin, out, ldout, (int)R,
+                       (int)Cc);
+    HIP_TRY(hipGetLastError());
+    return FLCE_OK;
+}
+
+template <typename T>
+int launch_ce_rows(T* Z, int64_t ldz, const int64_t* targets, int64_t rows, int64_t V,
+                   int64_t ignore_index, DeviceHeader* hdr, float* row_loss, hipStream_t s) {
+    const bool vec = aligned(Z, 16) && ((ldz * sizeof(T)) % 16 == 0);
+    if (vec)
+        hipLaunchKernelGGL((ce_rows_inplace_kernel<T, true>), dim3((unsigned)rows), dim3(RR_THREADS),
+                           0, s, Z, ldz, targets, (int)V, ignore_index, hdr, row_loss);
+    else
+        hipLaunchKernelGGL((ce_rows_inplace_kernel<T, false>), dim3((unsigned)rows),
+                           dim3(RR_THREADS), 0, s, Z, ldz, targets, (int)V, ignore_index, hdr,
+                           row_loss);
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(loss_accumulate_kernel, dim3(1), dim3(256), 0, s, row_loss, (int)rows, hdr);
+    HIP_TRY(hipGetLastError());
+    return FLCE_OK;
+}
+
+#define FLCE_TRY(expr)                 \
+    do {                               \
+        const int rc_ = (expr);        \
+        if (rc_ != FLCE_OK) return rc_; \
+    } while (0)
+
+template <typename T>
+int run_fwd_bwd(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t H, int64_t V,
+                int64_t ignore_index, float* loss, T* dX, T* dW, unsigned flags, const Plan& p,
+                char* ws, hipStream_t s) {
+    const bool want_dx = !(flags & FLCE_SKIP_DX), want_dw = !(flags & FLCE_SKIP_DW);
+    DeviceHeader* hdr = reinterpret_cast<DeviceHeader*>(ws + p.off_hdr);
+    float* row_loss = reinterpret_cast<float*>(ws + p.off_row_loss);
+    T* Z = reinterpret_cast<T*>(ws + p.off_z);
+    T* GT = reinterpret_cast<T*>(ws + p.off_gt);
+    T* WT = reinterpret_cast<T*>(ws + p.off_wt);
+    T* XT = reinterpret_cast<T*>(ws + p.off_xt);
+    float* dWacc = reinterpret_cast<float*>(ws + p.off_dwacc);
+
+    hipLaunchKernelGGL(count_valid_kernel, dim3(1), dim3(1024), 0, s, targets, BT, ignore_index,
+                       hdr);
+    HIP_TRY(hipGetLastError());
+    if (want_dx) FLCE_TRY(launch_transpose<T>(W, H, WT, p.ldz, V, H, s));   // WT[H x V]
+
+    for (int64_t c = 0; c < p.nchunks; ++c) {
+        const int64_t r0 = c * p.C;
+        const int64_t rows = (BT - r0 < p.C) ? BT - r0 : p.C;
+        const T* Xc = X + r0 * H;
+        // logits of the chunk: Z = X_c W^T
+        FLCE_TRY((launch_gemm_generic<T, T>(Xc, H, W, H, Z, p.ldz, rows, V, H, false, s)));
+        // loss and in-place dlogits
+        FLCE_TRY(launch_ce_rows<T>(Z, p.ldz, targets + r0, rows, V, ignore_index, hdr, row_loss, s));
+        // dX_c = G W  (as G [rows x V] times WT[H x V]^T)
+        if (want_dx)
+            FLCE_TRY((launch_gemm_generic<T, T>(Z, p.ldz, WT, p.ldz, dX + r0 * H, H, rows, H, V,
+                                                false, s)));
+        // dW (+)= G^T X_c  (as GT[V x rows] times XT[H x rows]^T)
+        if (want_dw) {
+            FLCE_TRY(launch_transpose<T>(Z, p.ldz, GT, p.ldc, rows, V, s));
+            FLCE_TRY(launch_transpose<T>(Xc, H, XT, p.ldc, rows, H, s));
+            if (p.fp32_dw_acc) {
+                FLCE_TRY((launch_gemm_generic<T, float>(GT, p.ldc, XT, p.ldc, dWacc, H, V, H, rows,
+                                                        c > 0, s)));
+            } else {
+                FLCE_TRY((launch_gemm_generic<T, T>(GT, p.ldc, XT, p.ldc, dW, H, V, H, rows, c > 0,
+                                                    s)));
+            }
+        }
+    }
+    hipLaunchKernelGGL(finalize_loss_kernel, dim3(1), dim3(64), 0, s, hdr, loss);
+    HIP_TRY(hipGetLastError());
+    if (want_dw && p.fp32_dw_acc) {
+        hipLaunchKernelGGL((cast_from_f32_kernel<T>), dim3(2048), dim3(256), 0, s, dWacc, dW,
+                           V * H);
+        HIP_TRY(hipGetLastError());
+    }
+    return FLCE_OK;
+}
+
+int check_dims(int64_t BT, int64_t H, int64_t V, int dtype) {
+    if (dtype != FLCE_F32 && dtype != FLCE_BF16) return FLCE_ERR_DTYPE;
+    if (BT <= 0 || H <= 0 || V <= 0 || BT > MAX_DIM || H > MAX_DIM || V > MAX_DIM)
+        return FLCE_ERR_SHAPE;
+    return FLCE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int flce_fwd_bwd_ex(const void* X, const void* W, const int64_t* targets, int64_t BT, int64_t H,
+                    int64_t V, int64_t ignore_index, int dtype, float* loss, void* dX, void* dW,
+                    unsigned flags, void* stream) {
+    FLCE_TRY(check_dims(BT, H, V, dtype));
+    if (flags & ~(unsigned)(FLCE_SKIP_DX | FLCE_SKIP_DW)) return FLCE_ERR_ARG;
+    const bool want_dx = !(flags & FLCE_SKIP_DX), want_dw = !(flags & FLCE_SKIP_DW);
+    if (!X || !W || !targets || !loss || (want_dx && !dX) || (want_dw && !dW)) return FLCE_ERR_NULL;
+    if (!aligned(X, 16) || !aligned(W, 16) || (want_dx && !aligned(dX, 16)) ||
+        (want_dw && !aligned(dW, 16)) || !aligned(targets, 8) || !aligned(loss, 4))
+        return FLCE_ERR_ALIGN;
+    if (ignore_index >= 0 && ignore_index < V) return FLCE_ERR_ARG;   // would shadow a class
+
+    const Plan p = make_plan(BT, H, V, dtype, g_budget);
+    char* ws = nullptr;
+    FLCE_TRY(acquire_workspace(p.total, &ws));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dtype == FLCE_F32)
+        return run_fwd_bwd<float>(static_cast<const float*>(X), static_cast<const float*>(W),
+                                  targets, BT, H, V, ignore_index, loss, static_cast<float*>(dX),
+                                  static_cast<float*>(dW), flags, p, ws, s);
+    return run_fwd_bwd<bf16_t>(static_cast<const bf16_t*>(X), static_cast<const bf16_t*>(W),
+                               targets, BT, H, V, ignore_index, loss, static_cast<bf16_t*>(dX),
+                               static_cast<bf16_t*>(dW), flags, p, ws, s);
+}
+
+int flce_fwd_bwd(const void* X, const void* W, const int64_t* targets, int64_t BT, int64_t H,
+                 int64_t V, int64_t ignore_index, int dtype, float* loss, void* dX, void* dW,
+                 void* stream) {
+    return flce_fwd_bwd_ex(X, W, targets, BT, H, V, ignore_index, dtype, loss, dX, dW, 0u, stream);
+}
+
+int flce_cross_entropy_inplace(void* Z, const int64_t* targets, int64_t BT, int64_t V, int64_t ldz,
+                               int64_t ignore_index, int dtype, float* loss, void* stream) {
+    FLCE_TRY(check_dims(BT, 1, V, dtype));
+    if (!Z || !targets || !loss) return FLCE_ERR_NULL;
+    if (ldz < V || ldz > MAX_DIM * 4) return FLCE_ERR_SHAPE;
+    if (!aligned(Z, elem_size(dtype)) || !aligned(targets, 8) || !aligned(loss, 4))
+        return FLCE_ERR_ALIGN;
+    if (ignore_index >= 0 && ignore_index < V) return FLCE_ERR_ARG;
+    const int64_t step = BT < CE_ROWS_PER_LAUNCH ? BT : CE_ROWS_PER_LAUNCH;
+    char* ws = nullptr;
+    FLCE_TRY(acquire_workspace(256 + (size_t)step * sizeof(float), &ws));
+    DeviceHeader* hdr = reinterpret_cast<DeviceHeader*>(ws);
+    float* row_loss = reinterpret_cast<float*>(ws + 256);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(count_valid_kernel, dim3(1), dim3(1024), 0, s, targets, BT, ignore_index,
+                       hdr);
+    HIP_TRY(hipGetLastError());
+    for (int64_t r0 = 0; r0 < BT; r0 += step) {
+        const int64_t rows = (BT - r0 < step) ? BT - r0 : step;
+        if (dtype == FLCE_F32)
+            FLCE_TRY(launch_ce_rows<float>(static_cast<float*>(Z) + r0 * ldz, ldz, targets + r0,
+                                           rows, V, ignore_index, hdr, row_loss, s));
+        else
+            FLCE_TRY(launch_ce_rows<bf16_t>(static_cast<bf16_t*>(Z) + r0 * ldz, ldz, targets + r0,
+                                            rows, V, ignore_index, hdr, row_loss, s));
+    }
+    hipLaunchKernelGGL(finalize_loss_kernel, dim3(1), dim3(64), 0, s, hdr, loss);
+    HIP_TRY(hipGetLastError());
+    return FLCE_OK;
+}
+
+size_t flce_workspace_bytes(int64_t BT, int64_t H, int64_t V, int dtype) {
+    if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
+    return make_plan(BT, H, V, dtype, g_budget).total;
+}
+
+size_t flce_workspace_bytes_max(int64_t H, int64_t V, int dtype) {
+    if (check_dims(1, H, V, dtype) != FLCE_OK) return 0;
+    return make_plan(0, H, V, dtype, g_budget, true).total;
+}
+
+int flce_set_workspace(void* ws, size_t bytes) {
+    if (ws && !aligned(ws, 256)) return FLCE_ERR_ALIGN;
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return FLCE_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_ws[dev].lent = ws;
+    g_ws[dev].lent_bytes = ws ? bytes : 0;
+    return FLCE_OK;
+}
+
+int flce_release_workspace(void) {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return FLCE_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceWorkspace& w = g_ws[dev];
+    if (w.own) {
+        HIP_TRY(hipDeviceSynchronize());
+        HIP_TRY(hipFree(w.own));
+        w.own = nullptr;
+        w.own_bytes = 0;
+    }
+    return FLCE_OK;
+}
+
+int flce_set_logits_budget_bytes(size_t bytes) {
+    if (bytes == 0) return FLCE_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_budget = bytes;
+    return FLCE_OK;
+}
+
+size_t flce_get_logits_budget_bytes(void) { return g_budget; }
+
+int64_t flce_chunk_rows(int64_t BT, int64_t H, int64_t V, int dtype) {
+    if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
+    return make_plan(BT, H, V, dtype, g_budget).C;
+}
+
+int64_t flce_num_chunks(int64_t BT, int64_t H, int64_t V, int dtype) {
+    if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
+    return make_plan(BT, H, V, dtype, g_budget).nchunks;
+}
+
+int64_t flce_paper_chunk_rows(int64_t BT, int64_t H, int64_t V) {
+    if (BT <= 0 || H <= 0 || V <= 0) return 0;
+    return paper_chunk_rows(BT, H, V);
+}
+
+size_t flce_full_logits_bytes(int64_t BT, int64_t V, int dtype) {
+    if (BT <= 0 || V <= 0 || (dtype != FLCE_F32 && dtype != FLCE_BF16)) return 0;
+    return (size_t)BT * (size_t)V * elem_size(dtype);
+}
+
+const char* flce_status_string(int status) {
+    switch (status) {
+        case FLCE_OK: return "ok";
+        case FLCE_ERR_NULL: return "a required pointer is NULL";
+        case FLCE_ERR_SHAPE: return "BT, H, V or a stride is out of range";
+        case FLCE_ERR_DTYPE: return "unknown dtype";
+        case FLCE_ERR_ALIGN: return "a pointer misses its required alignment";
+        case FLCE_ERR_WORKSPACE: return "workspace too small or allocation failed";
+        case FLCE_ERR_HIP: return "a HIP runtime call or kernel launch failed";
+        case FLCE_ERR_ARG: return "invalid argument";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

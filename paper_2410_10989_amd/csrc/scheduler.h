@@ -1,0 +1,79 @@
+// Host-side chunk scheduler and workspace layout.  Pure integer arithmetic, no
+// HIP calls, so it can be exercised on a machine without a GPU.
+//
+// The method bounds memory by projecting only a chunk of C rows at a time
+// (paper section 3.2, FLCE paragraph).  Here C is set by a byte budget for the
+// chunk's logits instead of the paper's power-of-two rule: on this chip each
+// chunk re-reads W twice and read-modify-writes the fp32 dW accumulator, so C
+// has to stay in the thousands for the products to remain compute bound.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+namespace flce {
+
+constexpr int64_t CHUNK_ALIGN = 256;   // chunk rows are a multiple of the GEMM macro tile
+
+inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+inline size_t elem_size(int dtype) { return dtype == 0 ? 4 : 2; }
+
+struct Plan {
+    int64_t C = 0;         // rows per chunk (last chunk may hold fewer)
+    int64_t nchunks = 0;
+    int64_t ldz = 0;       // row stride of the logits chunk, elements
+    int64_t ldc = 0;       // row stride of the row-transposed scratch, elements
+    bool fp32_dw_acc = false;   // dW is accumulated in an fp32 scratch and cast at the end
+    // byte offsets into the workspace
+    size_t off_hdr = 0, off_row_loss = 0, off_z = 0, off_gt = 0, off_wt = 0, off_xt = 0,
+           off_dwacc = 0, total = 0;
+};
+
+inline Plan make_plan(int64_t BT, int64_t H, int64_t V, int dtype, size_t budget_bytes,
+                      bool worst_case_bt = false) {
+    Plan p;
+    const size_t es = elem_size(dtype);
+    p.ldz = round_up(V, 64);
+    int64_t cmax = (int64_t)(budget_bytes / ((size_t)p.ldz * es));
+    cmax = cmax / CHUNK_ALIGN * CHUNK_ALIGN;
+    if (cmax < CHUNK_ALIGN) cmax = CHUNK_ALIGN;
+    if (worst_case_bt) {
+        p.C = cmax;
+        p.nchunks = 2;
+    } else if (BT <= cmax) {
+        p.C = BT;
+        p.nchunks = 1;
+    } else {
+        p.nchunks = (BT + cmax - 1) / cmax;
+        p.C = round_up((BT + p.nchunks - 1) / p.nchunks, CHUNK_ALIGN);   // even out the chunks
+        p.nchunks = (BT + p.C - 1) / p.C;
+    }
+    p.ldc = round_up(p.C, 64);
+    p.fp32_dw_acc = (dtype != 0) && p.nchunks > 1;
+
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off += (bytes + 255) / 256 * 256;
+        return at;
+    };
+    p.off_hdr = take(256);
+    p.off_row_loss = take((size_t)p.C * sizeof(float));
+    p.off_z = take((size_t)p.C * p.ldz * es);
+    p.off_gt = take((size_t)V * p.ldc * es);
+    p.off_wt = take((size_t)H * p.ldz * es);
+    p.off_xt = take((size_t)H * p.ldc * es);
+    p.off_dwacc = take(p.fp32_dw_acc ? (size_t)V * H * sizeof(float) : 0);
+    p.total = off;
+    return p;
+}
+
+// Paper's rule: chunk = 2^ceil(log2(ceil(BT / ceil(V / H)))).
+inline int64_t paper_chunk_rows(int64_t BT, int64_t H, int64_t V) {
+    const int64_t inc = (V + H - 1) / H;
+    const int64_t c = (BT + inc - 1) / inc;
+    int64_t p2 = 1;
+    while (p2 < c) p2 <<= 1;
+    return p2;
+}
+
+}  // namespace flce

@@ -1,0 +1,97 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every
+symbol the header declares, rejects bad arguments before touching the device,
+and the chunk scheduler keeps the workspace bounded independently of BT."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2410_10989_amd as flce
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "flce.h")).read()
+    return sorted(set(re.findall(r"FLCE_API[^;(]*?\b(flce_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert len(names) >= 14 and "flce_fwd_bwd" in names
+    L = flce.lib()
+    for n in names:
+        assert hasattr(L, n), f"libflce.so does not export {n}"
+
+
+def test_paper_chunk_rule_at_the_five_shapes():
+    # 2^ceil(log2(ceil(BT / ceil(V/H)))): paper section 3.2, FLCE paragraph.
+    shapes = [(256, 512, 4096), (4096, 4096, 32000), (8192, 4096, 128256),
+              (16384, 3584, 152064), (8192, 2304, 256000)]
+    assert [flce.flce_paper_chunk_rows(*s) for s in shapes] == [32, 512, 256, 512, 128]
+    assert flce.flce_paper_chunk_rows(1, 8, 8) == 1
+    assert flce.flce_paper_chunk_rows(100, 10, 10) == 128
+
+
+def test_memory_example_printed_in_the_paper():
+    vals = {}
+    for line in open(os.path.join(ROOT, "tests", "golden", "paper_values.txt")):
+        line = line.split("#")[0].strip()
+        if line:
+            k, v = line.split("=")
+            vals[k.strip()] = float(v)
+    n = flce.flce_full_logits_bytes(int(vals["logits_example_batch"] * vals["logits_example_seq"]),
+                                    int(vals["logits_example_vocab"]), flce.FLCE_BF16)
+    assert n == 8 * 4096 * 256000 * 2
+    assert round(n / 1e9, 1) == vals["logits_example_gigabytes"]
+
+
+@pytest.mark.parametrize("H,V", [(4096, 128256), (3584, 152064), (2304, 256000), (4096, 32000)])
+def test_workspace_is_bounded_independently_of_BT(H, V):
+    code = flce.FLCE_BF16
+    cap = flce.flce_workspace_bytes_max(H, V, code)
+    C = flce.flce_chunk_rows(10 ** 7, H, V, code)
+    sizes = [flce.flce_workspace_bytes(bt, H, V, code) for bt in (C, 2 * C, 4 * C, 8 * C, 64 * C + 3)]
+    assert all(0 < s <= cap for s in sizes)
+    assert len(set(sizes[1:])) == 1          # constant once BT exceeds one chunk
+    budget = flce.flce_get_logits_budget_bytes()
+    assert C % 256 == 0 and C * V * 2 <= budget
+    for bt in (1, 255, C, C + 1, 3 * C - 5):
+        c, n = flce.flce_chunk_rows(bt, H, V, code), flce.flce_num_chunks(bt, H, V, code)
+        assert c * n >= bt > c * (n - 1) and c <= max(C, 256)
+
+
+def test_bad_arguments_are_rejected_on_the_host():
+    L = flce.lib()
+    buf = (ctypes.c_char * 4096)()
+    a = ctypes.addressof(buf)
+    a += (-a) % 256
+    ok = dict(X=a, W=a + 256, t=a + 512, loss=a + 768, dX=a + 1024, dW=a + 1280)
+
+    def call(BT=4, H=8, V=16, ign=-100, dtype=1, **kw):
+        p = dict(ok, **kw)
+        return L.flce_fwd_bwd(p["X"], p["W"], p["t"], BT, H, V, ign, dtype, p["loss"], p["dX"],
+                              p["dW"], None)
+
+    assert call(X=None) == 1 and call(dW=None) == 1 and call(loss=None) == 1
+    assert call(BT=0) == 2 and call(V=-1) == 2 and call(H=2 ** 40) == 2
+    assert call(dtype=7) == 3
+    assert call(X=a + 2) == 4 and call(t=a + 516) == 4
+    assert call(ign=3) == 7
+    assert L.flce_fwd_bwd_ex(ok["X"], ok["W"], ok["t"], 4, 8, 16, -100, 1, ok["loss"], None, None,
+                             64, None) == 7
+    assert L.flce_set_logits_budget_bytes(0) == 7
+    assert L.flce_cross_entropy_inplace(None, a, 1, 1, 1, -100, 1, a, None) == 1
+    assert L.flce_cross_entropy_inplace(a, a, 4, 16, 8, -100, 1, a, None) == 2   # ldz < V
+    for s in range(8):
+        assert flce.status_string(s) not in ("", "unknown status")
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    X = torch.zeros(4, 8, dtype=torch.bfloat16)
+    W = torch.zeros(16, 8, dtype=torch.bfloat16)
+    t = torch.zeros(4, dtype=torch.int64)
+    with pytest.raises(ValueError):
+        flce.flce_fwd_bwd(X, W, t, loss=torch.zeros(()), dX=X.clone(), dW=W.clone())

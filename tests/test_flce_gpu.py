@@ -1,0 +1,126 @@
+"""Parity of the HIP path (called through the C ABI) with the fp64 CPU oracle,
+element by element, on seeded inputs at sizes the oracle finishes in seconds:
+several tiles, ragged tails, several chunks, and the degenerate cases."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from flce_testlib import TOL, assert_close, assert_loss, run_gpu, to_host, upload
+from oracle import flce_oracle as oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def check_full(w, flags=0):
+    import paper_2410_10989_amd as flce
+    print(f"case {w.name} BT={w.BT} H={w.H} V={w.V} {w.dtype} seed={w.seed} flags={flags} "
+          f"chunks={flce.flce_num_chunks(w.BT, w.H, w.V, flce.FLCE_BF16 if w.dtype == 'bf16' else flce.FLCE_F32)}",
+          flush=True)
+    ref = oracle.flce(w.X, w.W, w.targets, w.ignore_index)
+    loss, dX, dW = run_gpu(w, flags)
+    rl, rg = TOL[w.dtype]
+    assert_loss(loss, ref.loss, rl)
+    if not flags & flce.SKIP_DX:
+        assert_close("dX", to_host(dX), ref.dX, rg)
+        ign = w.targets == w.ignore_index
+        if ign.any():   # ignored rows are exact zeros
+            assert (to_host(dX)[ign] == 0).all()
+    if not flags & flce.SKIP_DW:
+        assert_close("dW", to_host(dW), ref.dW, rg)
+    return loss, dX, dW
+
+
+def test_config1_tiny_fp32():
+    check_full(workloads.make_config(1))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("BT,H,V,ignore", [
+    (300, 136, 1000, ("iid", 0.1)),     # ragged in every dimension, aligned K
+    (77, 100, 333, ("iid", 0.3)),       # H not a multiple of the vector width
+    (1, 64, 129, ("none",)),            # a single row
+    (129, 8, 2, ("iid", 0.2)),          # two classes
+    (513, 256, 2048, ("iid", 0.05)),    # tile-aligned except one trailing row
+    (640, 72, 4100, ("pad", 128, 60)),  # padding runs
+])
+def test_ragged_shapes(dtype, BT, H, V, ignore):
+    check_full(workloads.make(BT, H, V, dtype, ignore=ignore, seed=1000 + BT + V, name="ragged"))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_several_chunks_with_ragged_last_chunk(dtype):
+    # A budget of 256 rows of logits forces 3 chunks (256, 256, 1 rows); the
+    # result must be the one-chunk result within tolerance and match the oracle.
+    import paper_2410_10989_amd as flce
+    w = workloads.make(513, 192, 1536, dtype, ignore=("iid", 0.15), seed=4242, name="chunked")
+    old = flce.flce_get_logits_budget_bytes()
+    try:
+        flce.flce_set_logits_budget_bytes(256 * 1536 * (4 if dtype == "f32" else 2))
+        code = flce.FLCE_F32 if dtype == "f32" else flce.FLCE_BF16
+        assert flce.flce_num_chunks(w.BT, w.H, w.V, code) == 3
+        check_full(w)
+    finally:
+        flce.flce_set_logits_budget_bytes(old)
+
+
+def test_zipf_targets_medium_bf16():
+    check_full(workloads.make(1024, 512, 8192, "bf16", targets="zipf", ignore=("iid", 0.05),
+                              seed=99, name="zipf"))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_all_rows_ignored_gives_zeros(dtype):
+    w = workloads.make(130, 64, 300, dtype, seed=7, name="all_ignored")
+    w.targets[:] = w.ignore_index
+    loss, dX, dW = run_gpu(w)
+    assert loss == 0.0
+    assert (to_host(dX) == 0).all() and (to_host(dW) == 0).all()
+
+
+def test_skip_flags():
+    import paper_2410_10989_amd as flce
+    w = workloads.make(260, 128, 700, "bf16", ignore=("iid", 0.1), seed=31, name="skip")
+    check_full(w, flce.SKIP_DX)
+    check_full(w, flce.SKIP_DW)
+
+
+def test_runs_are_bitwise_reproducible():
+    w = workloads.make(700, 256, 3000, "bf16", ignore=("iid", 0.1), seed=55, name="repro")
+    a = run_gpu(w)
+    b = run_gpu(w)
+    assert a[0] == b[0]
+    assert torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
+
+
+def test_large_logits_do_not_overflow():
+    w = workloads.make(64, 128, 512, "f32", seed=8, name="large_logits", x_std=8.0, w_std=2.0)
+    ref = oracle.flce(w.X, w.W, w.targets, w.ignore_index)
+    loss, dX, dW = run_gpu(w)
+    assert_loss(loss, ref.loss, 1e-5)
+    assert_close("dX", to_host(dX), ref.dX, 1e-4)
+    assert_close("dW", to_host(dW), ref.dW, 1e-4)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("BT,V,pad", [(37, 1000, 0), (16, 4099, 5), (3, 7, 0), (200, 40960, 0)])
+def test_standalone_cross_entropy(dtype, BT, V, pad):
+    import paper_2410_10989_amd as flce
+    g = np.random.default_rng(BT * 7 + V)
+    Z = (g.standard_normal((BT, V)) * 2.0).astype(np.float32)
+    if dtype == "bf16":
+        workloads.round_to_bf16(Z)
+    t = g.integers(0, V, size=BT).astype(np.int64)
+    t[::5] = -100
+    ref_loss, ref_G, _ = oracle.cross_entropy(Z.astype(np.float64), t, -100)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    buf = torch.zeros((BT, V + pad), dtype=tdt, device="cuda")
+    buf[:, :V] = torch.from_numpy(Z).cuda().to(tdt)
+    view = buf[:, :V]
+    loss = flce.flce_cross_entropy_inplace(view, torch.from_numpy(t).cuda(), -100)
+    torch.cuda.synchronize()
+    rl, rg = TOL[dtype]
+    assert_loss(float(loss.item()), ref_loss, rl)
+    assert_close("dZ", to_host(view), ref_G, rg)
+    if pad:
+        assert (to_host(buf[:, V:]) == 0).all()   # the row padding is not touched
