@@ -1,0 +1,152 @@
+"""Benchmark of the fused linear cross-entropy forward+backward on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--no-cpu-baseline]
+
+One step = one pass of the whole hot path (count, chunked logits GEMM, in-place
+cross entropy, dX GEMM, dW GEMM, finalize) over one synthetic batch that is
+already resident in HBM.  Prints ONE JSON line: tokens/s for forward+backward,
+the roofline of the dominant kernel (per-launch algorithmic flops over its
+average launch time, HIP events on the launch stream), and the CPU oracle timed
+on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense matrix peaks
+HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs, scaled by a copy kernel of known size; see profiles/.  None
+# until such a run has been recorded for the current kernel.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3, help="workload 1-5 (3 = Llama-3-8B lm_head)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-rows", type=int, default=1024)
+    ap.add_argument("--budget-mib", type=int, default=0, help="logits chunk budget override")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the path is a single-GPU kernel "
+              "pipeline; no collectives are part of it). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2410_10989_amd as flce
+    import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    if args.budget_mib:
+        flce.flce_set_logits_budget_bytes(args.budget_mib << 20)
+
+    t0 = time.time()
+    w = workloads.make_config(args.config)
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    code = flce.FLCE_BF16 if w.dtype == "bf16" else flce.FLCE_F32
+
+    def up(a):
+        if w.dtype == "bf16":
+            return torch.from_numpy(workloads.bf16_bits(a).view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(a).cuda()
+
+    X, W, t = up(w.X), up(w.W), torch.from_numpy(w.targets).cuda()
+    dX, dW = torch.empty_like(X), torch.empty_like(W)
+    loss = torch.empty((), dtype=torch.float32, device="cuda")
+    print(f"# inputs {w.name} BT={w.BT} H={w.H} V={w.V} {w.dtype} generated+uploaded in "
+          f"{time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+
+    def step():
+        flce.flce_fwd_bwd(X, W, t, w.ignore_index, loss=loss, dX=dX, dW=dW)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    flce.flce_timing_enable(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    flce.flce_timing_enable(False)
+    kt = flce.flce_timing_collect()
+    ms_per_step = (t2 - t1) * 1e3 / args.steps
+    tokens_per_s = w.BT / (ms_per_step * 1e-3)
+
+    flops_step = 6.0 * w.BT * w.H * w.V
+    tflops = flops_step / (ms_per_step * 1e-3) / 1e12
+    peak = MFMA_PEAK_TFLOPS[w.dtype]
+
+    # dominant kernel class = the one with the largest total time
+    gemm_kinds = ("logits_gemm", "dx_gemm", "dw_gemm")
+    dom = max(gemm_kinds, key=lambda k: kt[k][0])
+    nchunks = flce.flce_num_chunks(w.BT, w.H, w.V, code)
+    dom_ms, dom_n = kt[dom]
+    flops_per_launch = 2.0 * w.BT * w.H * w.V * args.steps / max(dom_n, 1)   # mean over its launches
+    dom_avg_ms = dom_ms / max(dom_n, 1)
+    achieved = flops_per_launch / (dom_avg_ms * 1e-3) / 1e12 if dom_n else 0.0
+    ce_ms, ce_n = kt["ce_rows"]
+    ce_gbs = (2.0 * w.BT * w.V * (2 if w.dtype == "bf16" else 4) * args.steps) / (ce_ms * 1e-3) / 1e9 if ce_n else 0.0
+
+    out = {
+        "metric": "FLCE fwd+bwd tokens/s",
+        "value": tokens_per_s,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"config{args.config}:{w.name}", "BT": w.BT, "H": w.H, "V": w.V,
+                   "ignore_frac": round(1 - w.n_valid / w.BT, 4), "chunk_rows":
+                   flce.flce_chunk_rows(w.BT, w.H, w.V, code), "chunks": nchunks,
+                   "logits_budget_mib": flce.flce_get_logits_budget_bytes() >> 20},
+        "tflops_over_6BTHV": tflops,
+        "mfma_util_frac_of_peak": tflops / peak,
+        "peak_extra_hbm_mb": flce.flce_workspace_bytes(w.BT, w.H, w.V, code) / 1e6,
+        "full_logits_avoided_mb": flce.flce_full_logits_bytes(w.BT, w.V, code) / 1e6,
+        "loss": float(loss.item()),
+        "kernel_ms_per_step": {k: kt[k][0] / args.steps for k in kt},
+        "ce_rows_hbm_gbs": ce_gbs,
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": peak,
+                     "unit": "TFLOP/s", "frac": achieved / peak,
+                     "avg_launch_ms": dom_avg_ms, "launches": dom_n,
+                     "flops_per_launch": flops_per_launch,
+                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import flce_oracle
+        n = min(args.cpu_sample_rows, w.BT)
+        tc = time.perf_counter()
+        flce_oracle.flce(w.X[:n], w.W, w.targets[:n], w.ignore_index)
+        dt = time.perf_counter() - tc
+        out["cpu_baseline"] = {"value": n / dt, "unit": "tokens/s", "cores": flce_oracle.threads(),
+                               "kind": "oracle",
+                               "sample": f"first {n} of {w.BT} rows of the same workload, full fp64 "
+                                         f"forward+backward, {dt:.1f} s"}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -134,6 +134,26 @@ FLCE_API int64_t flce_paper_chunk_rows(int64_t BT, int64_t H, int64_t V);
 /* Bytes of the full logits tensor BT x V that is never materialised. */
 FLCE_API size_t flce_full_logits_bytes(int64_t BT, int64_t V, int dtype);
 
+/*
+ * Per-kernel timing for benchmarks (not for production loops).  While enabled,
+ * every kernel launch of flce_fwd_bwd / flce_cross_entropy_inplace is bracketed
+ * by HIP events on the call's own stream and booked under an flce_kernel_kind.
+ * flce_timing_collect waits for the recorded events, adds up milliseconds and
+ * launch counts per kind into the caller's HOST arrays (FLCE_NUM_KINDS entries
+ * each) and clears the records.  At most 8192 launches are kept between two
+ * collects; later ones are not recorded.
+ */
+typedef enum {
+    FLCE_KIND_LOGITS_GEMM = 0, /* Z_c = X_c W^T                      */
+    FLCE_KIND_CE_ROWS = 1,     /* loss + in-place dlogits             */
+    FLCE_KIND_DX_GEMM = 2,     /* dX_c = G_c W                        */
+    FLCE_KIND_DW_GEMM = 3,     /* dW += G_c^T X_c                     */
+    FLCE_KIND_OTHER = 4,       /* count, transposes, casts, finalize  */
+    FLCE_NUM_KINDS = 5
+} flce_kernel_kind;
+FLCE_API int flce_timing_enable(int on);
+FLCE_API int flce_timing_collect(double* total_ms, int64_t* launches);
+
 FLCE_API const char* flce_status_string(int status);
 
 #ifdef __cplusplus

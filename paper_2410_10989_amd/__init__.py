@@ -9,7 +9,8 @@ from .binding import (  # noqa: F401
     flce_get_logits_budget_bytes, flce_num_chunks, flce_paper_chunk_rows,
     flce_release_workspace, flce_set_logits_budget_bytes, flce_set_workspace,
     flce_workspace_bytes,
-    flce_workspace_bytes_max, lib, status_string,
+    flce_workspace_bytes_max, lib, status_string, flce_timing_enable, flce_timing_collect,
+    KERNEL_KINDS,
 )
 
 flce_status_string = status_string

@@ -48,6 +48,8 @@ def lib() -> ctypes.CDLL:
             "flce_num_chunks": ([i64, i64, i64, ci], i64),
             "flce_paper_chunk_rows": ([i64, i64, i64], i64),
             "flce_full_logits_bytes": ([i64, i64, ci], sz),
+            "flce_timing_enable": ([ci], ci),
+            "flce_timing_collect": ([p, p], ci),
             "flce_status_string": ([ci], ctypes.c_char_p),
         }
         for name, (args, res) in sigs.items():
@@ -185,3 +187,19 @@ def flce_paper_chunk_rows(BT, H, V) -> int:
 
 def flce_full_logits_bytes(BT, V, dtype) -> int:
     return int(lib().flce_full_logits_bytes(BT, V, _DTYPES.get(dtype, dtype)))
+
+
+KERNEL_KINDS = ("logits_gemm", "ce_rows", "dx_gemm", "dw_gemm", "other")
+
+
+def flce_timing_enable(on: bool):
+    _check(lib().flce_timing_enable(1 if on else 0), "flce_timing_enable")
+
+
+def flce_timing_collect() -> dict:
+    """{kind: (total_ms, launches)} of the launches recorded since the last collect."""
+    n = len(KERNEL_KINDS)
+    ms = (ctypes.c_double * n)()
+    cnt = (ctypes.c_int64 * n)()
+    _check(lib().flce_timing_collect(ctypes.addressof(ms), ctypes.addressof(cnt)), "flce_timing_collect")
+    return {k: (float(ms[i]), int(cnt[i])) for i, k in enumerate(KERNEL_KINDS)}

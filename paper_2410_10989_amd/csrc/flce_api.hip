@@ -3,6 +3,7 @@
 // meaning of every argument are in include/flce.h.
 #include <hip/hip_runtime.h>
 #include <mutex>
+#include <vector>
 
 #include "../../include/flce.h"
 #include "flce_device.h"
@@ -29,6 +30,36 @@ struct DeviceWorkspace {
 std::mutex g_mutex;
 DeviceWorkspace g_ws[MAX_DEVICES];
 size_t g_budget = (size_t)1 << 30;
+
+// ---- optional per-kernel timing (benchmarks only) ----
+struct TimingRecord {
+    hipEvent_t start, stop;
+    int kind;
+};
+constexpr int MAX_TIMING_RECORDS = 8192;
+bool g_timing_on = false;
+std::vector<TimingRecord> g_records;
+
+struct ScopedKernelTimer {
+    hipStream_t stream;
+    bool active = false;
+    TimingRecord rec{};
+    ScopedKernelTimer(int kind, hipStream_t s) : stream(s) {
+        if (!g_timing_on || (int)g_records.size() >= MAX_TIMING_RECORDS) return;
+        if (hipEventCreate(&rec.start) != hipSuccess) return;
+        if (hipEventCreate(&rec.stop) != hipSuccess) {
+            (void)hipEventDestroy(rec.start);
+            return;
+        }
+        rec.kind = kind;
+        active = (hipEventRecord(rec.start, stream) == hipSuccess);
+    }
+    ~ScopedKernelTimer() {
+        if (!active) return;
+        (void)hipEventRecord(rec.stop, stream);
+        g_records.push_back(rec);
+    }
+};
 
 #define HIP_TRY(expr)                          \
     do {                                       \
@@ -71,9 +102,10 @@ int acquire_workspace(size_t need, char** out) {
 
 // C[M x N] (+)= A[M x K] * B[N x K]^T on the generic guarded kernel.
 template <typename T, typename OutT>
-int launch_gemm_generic(const T* A, int64_t lda, const T* B, int64_t ldb, OutT* C, int64_t ldc,
-                        int64_t M, int64_t N, int64_t K, bool accum, hipStream_t s) {
+int launch_gemm_generic(int kind, const T* A, int64_t lda, const T* B, int64_t ldb, OutT* C,
+                        int64_t ldc, int64_t M, int64_t N, int64_t K, bool accum, hipStream_t s) {
     if (M <= 0 || N <= 0) return FLCE_OK;
+    ScopedKernelTimer timer(kind, s);
     constexpr int VEC = GGTraits<T>::VEC;
     const bool al = (K % VEC == 0) && (lda % VEC == 0) && (ldb % VEC == 0) && aligned(A, 16) &&
                     aligned(B, 16);
@@ -96,6 +128,7 @@ template <typename T>
 int launch_transpose(const T* in, int64_t ldin, T* out, int64_t ldout, int64_t R, int64_t Cc,
                      hipStream_t s) {
     if (R <= 0 || Cc <= 0) return FLCE_OK;
+    ScopedKernelTimer timer(FLCE_KIND_OTHER, s);
     dim3 grid((unsigned)((Cc + 63) / 64), (unsigned)((R + 63) / 64));
     hipLaunchKernelGGL((transpose_kernel<T>), grid, dim3(256), 0, s, in, ldin, out, ldout, (int)R,
                        (int)Cc);
@@ -107,6 +140,7 @@ template <typename T>
 int launch_ce_rows(T* Z, int64_t ldz, const int64_t* targets, int64_t rows, int64_t V,
                    int64_t ignore_index, DeviceHeader* hdr, float* row_loss, hipStream_t s) {
     const bool vec = aligned(Z, 16) && ((ldz * sizeof(T)) % 16 == 0);
+    ScopedKernelTimer timer(FLCE_KIND_CE_ROWS, s);
     if (vec)
         hipLaunchKernelGGL((ce_rows_inplace_kernel<T, true>), dim3((unsigned)rows), dim3(RR_THREADS),
                            0, s, Z, ldz, targets, (int)V, ignore_index, hdr, row_loss);
@@ -149,22 +183,22 @@ int run_fwd_bwd(const T* X, const T* W, const int64_t* targets, int64_t BT, int6
         const int64_t rows = (BT - r0 < p.C) ? BT - r0 : p.C;
         const T* Xc = X + r0 * H;
         // logits of the chunk: Z = X_c W^T
-        FLCE_TRY((launch_gemm_generic<T, T>(Xc, H, W, H, Z, p.ldz, rows, V, H, false, s)));
+        FLCE_TRY((launch_gemm_generic<T, T>(FLCE_KIND_LOGITS_GEMM, Xc, H, W, H, Z, p.ldz, rows, V, H, false, s)));
         // loss and in-place dlogits
         FLCE_TRY(launch_ce_rows<T>(Z, p.ldz, targets + r0, rows, V, ignore_index, hdr, row_loss, s));
         // dX_c = G W  (as G [rows x V] times WT[H x V]^T)
         if (want_dx)
-            FLCE_TRY((launch_gemm_generic<T, T>(Z, p.ldz, WT, p.ldz, dX + r0 * H, H, rows, H, V,
+            FLCE_TRY((launch_gemm_generic<T, T>(FLCE_KIND_DX_GEMM, Z, p.ldz, WT, p.ldz, dX + r0 * H, H, rows, H, V,
                                                 false, s)));
         // dW (+)= G^T X_c  (as GT[V x rows] times XT[H x rows]^T)
         if (want_dw) {
             FLCE_TRY(launch_transpose<T>(Z, p.ldz, GT, p.ldc, rows, V, s));
             FLCE_TRY(launch_transpose<T>(Xc, H, XT, p.ldc, rows, H, s));
             if (p.fp32_dw_acc) {
-                FLCE_TRY((launch_gemm_generic<T, float>(GT, p.ldc, XT, p.ldc, dWacc, H, V, H, rows,
+                FLCE_TRY((launch_gemm_generic<T, float>(FLCE_KIND_DW_GEMM, GT, p.ldc, XT, p.ldc, dWacc, H, V, H, rows,
                                                         c > 0, s)));
             } else {
-                FLCE_TRY((launch_gemm_generic<T, T>(GT, p.ldc, XT, p.ldc, dW, H, V, H, rows, c > 0,
+                FLCE_TRY((launch_gemm_generic<T, T>(FLCE_KIND_DW_GEMM, GT, p.ldc, XT, p.ldc, dW, H, V, H, rows, c > 0,
                                                     s)));
             }
         }
@@ -172,6 +206,7 @@ int run_fwd_bwd(const T* X, const T* W, const int64_t* targets, int64_t BT, int6
     hipLaunchKernelGGL(finalize_loss_kernel, dim3(1), dim3(64), 0, s, hdr, loss);
     HIP_TRY(hipGetLastError());
     if (want_dw && p.fp32_dw_acc) {
+        ScopedKernelTimer timer(FLCE_KIND_OTHER, s);
         hipLaunchKernelGGL((cast_from_f32_kernel<T>), dim3(2048), dim3(256), 0, s, dWacc, dW,
                            V * H);
         HIP_TRY(hipGetLastError());
@@ -315,6 +350,37 @@ int64_t flce_paper_chunk_rows(int64_t BT, int64_t H, int64_t V) {
 size_t flce_full_logits_bytes(int64_t BT, int64_t V, int dtype) {
     if (BT <= 0 || V <= 0 || (dtype != FLCE_F32 && dtype != FLCE_BF16)) return 0;
     return (size_t)BT * (size_t)V * elem_size(dtype);
+}
+
+int flce_timing_enable(int on) {
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_timing_on = (on != 0);
+    return FLCE_OK;
+}
+
+int flce_timing_collect(double* total_ms, int64_t* launches) {
+    if (!total_ms || !launches) return FLCE_ERR_NULL;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    for (int k = 0; k < FLCE_NUM_KINDS; ++k) {
+        total_ms[k] = 0.0;
+        launches[k] = 0;
+    }
+    int rc = FLCE_OK;
+    for (TimingRecord& r : g_records) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.stop) == hipSuccess &&
+            hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
+            total_ms[r.kind] += ms;
+            launches[r.kind] += 1;
+        } else {
+            (void)hipGetLastError();
+            rc = FLCE_ERR_HIP;
+        }
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    g_records.clear();
+    return rc;
 }
 
 const char* flce_status_string(int status) {
