@@ -7,6 +7,7 @@
 
 #include "../../include/flce.h"
 #include "flce_device.h"
+#include "gemm_bf16_nt.h"
 #include "gemm_generic.h"
 #include "misc_kernels.h"
 #include "rowreduce.h"
@@ -124,6 +125,33 @@ int launch_gemm_generic(int kind, const T* A, int64_t lda, const T* B, int64_t l
     return FLCE_OK;
 }
 
+// Tuned bf16 kernel when the operands allow it, the guarded kernel otherwise.
+template <typename T, typename OutT>
+int launch_gemm(int kind, const T* A, int64_t lda, const T* B, int64_t ldb, OutT* C, int64_t ldc,
+                int64_t M, int64_t N, int64_t K, bool accum, hipStream_t s) {
+    if (M <= 0 || N <= 0) return FLCE_OK;
+    if constexpr (sizeof(T) == 2) {
+        const int64_t ld_max = lda > ldb ? lda : ldb;
+        const bool fast = (K > 0) && (K % FG_BK == 0) && (lda % 8 == 0) && (ldb % 8 == 0) &&
+                          aligned(A, 16) && aligned(B, 16) &&
+                          ((FG_BM * ld_max + K) * 2 < ((int64_t)1 << 31));
+        if (fast) {
+            ScopedKernelTimer timer(kind, s);
+            FGArgs a{A, lda, B, ldb, C, ldc, (int)M, (int)N, (int)K,
+                     (int)((M + FG_BM - 1) / FG_BM), (int)((N + FG_BN - 1) / FG_BN)};
+            const int64_t total = (int64_t)a.tiles_m * a.tiles_n;
+            const dim3 grid((unsigned)((total + FG_XCDS - 1) / FG_XCDS * FG_XCDS));
+            if (accum)
+                hipLaunchKernelGGL((gemm_bf16_nt_256<OutT, true, 1>), grid, dim3(FG_THREADS), 0, s, a);
+            else
+                hipLaunchKernelGGL((gemm_bf16_nt_256<OutT, false, 1>), grid, dim3(FG_THREADS), 0, s, a);
+            HIP_TRY(hipGetLastError());
+            return FLCE_OK;
+        }
+    }
+    return launch_gemm_generic<T, OutT>(kind, A, lda, B, ldb, C, ldc, M, N, K, accum, s);
+}
+
 template <typename T>
 int launch_transpose(const T* in, int64_t ldin, T* out, int64_t ldout, int64_t R, int64_t Cc,
                      hipStream_t s) {
@@ -183,22 +211,22 @@ int run_fwd_bwd(const T* X, const T* W, const int64_t* targets, int64_t BT, int6
         const int64_t rows = (BT - r0 < p.C) ? BT - r0 : p.C;
         const T* Xc = X + r0 * H;
         // logits of the chunk: Z = X_c W^T
-        FLCE_TRY((launch_gemm_generic<T, T>(FLCE_KIND_LOGITS_GEMM, Xc, H, W, H, Z, p.ldz, rows, V, H, false, s)));
+        FLCE_TRY((launch_gemm<T, T>(FLCE_KIND_LOGITS_GEMM, Xc, H, W, H, Z, p.ldz, rows, V, H, false, s)));
         // loss and in-place dlogits
         FLCE_TRY(launch_ce_rows<T>(Z, p.ldz, targets + r0, rows, V, ignore_index, hdr, row_loss, s));
         // dX_c = G W  (as G [rows x V] times WT[H x V]^T)
         if (want_dx)
-            FLCE_TRY((launch_gemm_generic<T, T>(FLCE_KIND_DX_GEMM, Z, p.ldz, WT, p.ldz, dX + r0 * H, H, rows, H, V,
+            FLCE_TRY((launch_gemm<T, T>(FLCE_KIND_DX_GEMM, Z, p.ldz, WT, p.ldz, dX + r0 * H, H, rows, H, V,
                                                 false, s)));
         // dW (+)= G^T X_c  (as GT[V x rows] times XT[H x rows]^T)
         if (want_dw) {
             FLCE_TRY(launch_transpose<T>(Z, p.ldz, GT, p.ldc, rows, V, s));
             FLCE_TRY(launch_transpose<T>(Xc, H, XT, p.ldc, rows, H, s));
             if (p.fp32_dw_acc) {
-                FLCE_TRY((launch_gemm_generic<T, float>(FLCE_KIND_DW_GEMM, GT, p.ldc, XT, p.ldc, dWacc, H, V, H, rows,
+                FLCE_TRY((launch_gemm<T, float>(FLCE_KIND_DW_GEMM, GT, p.ldc, XT, p.ldc, dWacc, H, V, H, rows,
                                                         c > 0, s)));
             } else {
-                FLCE_TRY((launch_gemm_generic<T, T>(FLCE_KIND_DW_GEMM, GT, p.ldc, XT, p.ldc, dW, H, V, H, rows, c > 0,
+                FLCE_TRY((launch_gemm<T, T>(FLCE_KIND_DW_GEMM, GT, p.ldc, XT, p.ldc, dW, H, V, H, rows, c > 0,
                                                     s)));
             }
         }

@@ -43,6 +43,9 @@ def test_config1_tiny_fp32():
     (129, 8, 2, ("iid", 0.2)),          # two classes
     (513, 256, 2048, ("iid", 0.05)),    # tile-aligned except one trailing row
     (640, 72, 4100, ("pad", 128, 60)),  # padding runs
+    (768, 320, 1344, ("iid", 0.1)),     # tuned-kernel path: K multiples of 64, ragged tile edges
+    (256, 64, 256, ("none",)),          # tuned-kernel path: exactly one macro tile
+    (832, 192, 2112, ("iid", 0.5)),     # tuned-kernel path, half the rows ignored
 ])
 def test_ragged_shapes(dtype, BT, H, V, ignore):
     check_full(workloads.make(BT, H, V, dtype, ignore=ignore, seed=1000 + BT + V, name="ragged"))
