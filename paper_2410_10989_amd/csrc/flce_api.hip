@@ -134,17 +134,26 @@ int launch_gemm(int kind, const T* A, int64_t lda, const T* B, int64_t ldb, OutT
         const int64_t ld_max = lda > ldb ? lda : ldb;
         const bool fast = (K > 0) && (K % FG_BK == 0) && (lda % 8 == 0) && (ldb % 8 == 0) &&
                           aligned(A, 16) && aligned(B, 16) &&
-                          ((FG_BM * ld_max + K) * 2 < ((int64_t)1 << 31));
-        if (fast) {
+                          ((FG_BM * ld_max + K + 256) * 2 < ((int64_t)1 << 31)) &&
+                          (FG_BM * ldc * (int64_t)sizeof(OutT) < ((int64_t)1 << 31));
+        // accumulation only ever targets the fp32 dW scratch
+        if (fast && (!accum || sizeof(OutT) == 4)) {
             ScopedKernelTimer timer(kind, s);
             FGArgs a{A, lda, B, ldb, C, ldc, (int)M, (int)N, (int)K,
                      (int)((M + FG_BM - 1) / FG_BM), (int)((N + FG_BN - 1) / FG_BN)};
             const int64_t total = (int64_t)a.tiles_m * a.tiles_n;
             const dim3 grid((unsigned)((total + FG_XCDS - 1) / FG_XCDS * FG_XCDS));
-            if (accum)
-                hipLaunchKernelGGL((gemm_bf16_nt_256<OutT, true, 1>), grid, dim3(FG_THREADS), 0, s, a);
-            else
+            if constexpr (sizeof(OutT) == 4) {
+                if (accum) {
+                    hipLaunchKernelGGL((gemm_bf16_nt_256<OutT, true, 1>), grid, dim3(FG_THREADS), 0, s,
+                                       a);
+                    HIP_TRY(hipGetLastError());
+                    return FLCE_OK;
+                }
+            }
+            {
                 hipLaunchKernelGGL((gemm_bf16_nt_256<OutT, false, 1>), grid, dim3(FG_THREADS), 0, s, a);
+            }
             HIP_TRY(hipGetLastError());
             return FLCE_OK;
         }
