@@ -145,14 +145,14 @@ int launch_gemm(int kind, const T* A, int64_t lda, const T* B, int64_t ldb, OutT
             const dim3 grid((unsigned)((total + FG_XCDS - 1) / FG_XCDS * FG_XCDS));
             if constexpr (sizeof(OutT) == 4) {
                 if (accum) {
-                    hipLaunchKernelGGL((gemm_bf16_nt_256<OutT, true, 1>), grid, dim3(FG_THREADS), 0, s,
+                    hipLaunchKernelGGL((gemm_bf16_nt_256<OutT, true>), grid, dim3(FG_THREADS), 0, s,
                                        a);
                     HIP_TRY(hipGetLastError());
                     return FLCE_OK;
                 }
             }
             {
-                hipLaunchKernelGGL((gemm_bf16_nt_256<OutT, false, 1>), grid, dim3(FG_THREADS), 0, s, a);
+                hipLaunchKernelGGL((gemm_bf16_nt_256<OutT, false>), grid, dim3(FG_THREADS), 0, s, a);
             }
             HIP_TRY(hipGetLastError());
             return FLCE_OK;

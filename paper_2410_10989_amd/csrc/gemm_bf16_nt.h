@@ -7,17 +7,23 @@
 //  - workgroup = 256 threads = 4 wavefronts (2 x 2); macro tile 256 x 256, K step
 //    64; each wavefront owns 128 x 128 = 4 x 4 MFMA tiles, i.e. 256 fp32
 //    accumulator registers per lane (one wavefront per SIMD, full register file).
-//  - global -> LDS directly (buffer_load_dwordx4 ... lds), two LDS stages of
-//    64 KB (of the CU's 160 KB): while the matrix cores work on stage t, tile t+1
-//    streams into the other stage; one workgroup barrier per K step.  The buffer
-//    descriptor's byte range makes rows beyond M / N read as zero, offsets stay
-//    32-bit, and no vector registers or LDS write instructions are spent on
-//    staging.
+//  - global -> LDS directly (buffer_load_dwordx4 ... lds): no vector registers
+//    and no LDS write instructions are spent on staging.  The buffer descriptor's
+//    byte range makes rows beyond M / N read as zero and keeps offsets 32-bit.
+//  - the whole 160 KB LDS of the CU is a ring of five 32 KB slots, each holding
+//    the A tile or the B tile (256 rows x 64 bf16) of one K step, filled in the
+//    order A0 B0 A1 B1 A2 ...  While step t is multiplied, B(t+1) and A(t+2)
+//    stream in, so the loads run up to two steps ahead and the memory pipe is
+//    fed continuously instead of in one burst per step; one workgroup barrier
+//    per K step, which waits for all but the youngest slot (s_waitcnt vmcnt(8)).
+//    What limits this kernel next to the matrix pipe is L2 bandwidth: a 256 x 256
+//    tile needs 128 B per row and step from L2, 16 TB/s at 2 PFLOP/s.
 //  - LDS rows are 128 B (64 bf16); the eight 16-byte pieces of a row are XOR
-//    swizzled with the row number so that ds_read_b128 of one K piece over 32
+//    swizzled with (row / 2) % 8 so that ds_read_b128 of one K piece over
 //    consecutive rows (the MFMA operand pattern) spreads over all banks.
 //  - operand fragments are double buffered in registers across the four K=16
-//    sub-steps and across the barrier, so LDS latency hides behind MFMAs.
+//    sub-steps; the last sub-step of a tile runs behind the barrier while the
+//    first fragments of the next tile arrive.
 //  - workgroup id -> tile: ids are dealt round-robin to the 8 XCDs, so id%8
 //    selects the XCD and each XCD walks its own contiguous span of a grouped
 //    (8 tile rows at a time) tile order; tiles that run together on one XCD
@@ -33,9 +39,9 @@
 namespace flce {
 
 constexpr int FG_BM = 256, FG_BN = 256, FG_BK = 64, FG_THREADS = 256;
-constexpr int FG_TILE_BYTES = FG_BM * FG_BK * 2;    // one operand, one stage: 32 KB
-constexpr int FG_STAGE_BYTES = 2 * FG_TILE_BYTES;   // A + B
-constexpr int FG_LDS_BYTES = 2 * FG_STAGE_BYTES;    // two stages: 128 KB
+constexpr int FG_TILE_BYTES = FG_BM * FG_BK * 2;    // one operand tile of one K step: 32 KB
+constexpr int FG_SLOTS = 5;                         // ring of operand-tile slots
+constexpr int FG_LDS_BYTES = FG_SLOTS * FG_TILE_BYTES;   // 160 KB: the whole LDS of a CU
 constexpr int FG_GROUP_M = 8;
 constexpr int FG_XCDS = 8;
 
@@ -55,7 +61,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t fg_make_rsrc(const void* base,
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
 
-template <typename OutT, bool ACCUM, int SWS>
+template <typename OutT, bool ACCUM>
 __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_nt_256(FGArgs a) {
     __shared__ __attribute__((aligned(16))) unsigned char smem[FG_LDS_BYTES];
 
@@ -87,7 +93,7 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_nt_256(FGArgs a) {
     const __amdgpu_buffer_rsrc_t rsrc_b =
         fg_make_rsrc(a.B + (int64_t)n0 * a.ldb, (uint32_t)rows_b * (uint32_t)a.ldb * 2u);
     const int ld_row = tid >> 3;                                   // 0..31
-    const int ld_piece = (tid & 7) ^ ((ld_row >> SWS) & 7);        // logical piece fetched
+    const int ld_piece = (tid & 7) ^ ((ld_row >> 1) & 7);        // logical piece fetched
     int off_a[8], off_b[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -96,42 +102,47 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_nt_256(FGArgs a) {
     }
     const int uwave = __builtin_amdgcn_readfirstlane(wave);
     typedef __attribute__((address_space(3))) void* lds_ptr_t;
-    // quad r < 8: A rows 32r.., r >= 8: B rows 32(r-8)..
-    auto gload = [&](int stage, int kt, int r_lo, int r_hi) {
+    // The ring: operand tiles are loaded in the order A0 B0 A1 B1 A2 ... and item
+    // number n lives in slot n % 5.  8 loads per wavefront fill one slot.
+    auto gload_a = [&](int kt, int slot) {
         const int soff = kt * (FG_BK * 2);
+        unsigned char* dst = smem + slot * FG_TILE_BYTES + uwave * 1024;
 #pragma unroll
-        for (int r = r_lo; r < r_hi; ++r) {
-            unsigned char* dst = smem + stage * FG_STAGE_BYTES + (r >> 3) * FG_TILE_BYTES +
-                                 (r & 7) * 4096 + uwave * 1024;
-            if (r < 8)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lds_ptr_t)dst, 16, off_a[r], soff, 0, 0);
-            else
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_ptr_t)dst, 16, off_b[r - 8], soff, 0, 0);
-        }
+        for (int r = 0; r < 8; ++r)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lds_ptr_t)(dst + r * 4096), 16, off_a[r],
+                                                     soff, 0, 0);
+    };
+    auto gload_b = [&](int kt, int slot) {
+        const int soff = kt * (FG_BK * 2);
+        unsigned char* dst = smem + slot * FG_TILE_BYTES + uwave * 1024;
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_ptr_t)(dst + r * 4096), 16, off_b[r],
+                                                     soff, 0, 0);
     };
 
     // ---- LDS side: MFMA operand fragments ----
+    // lane l of a fragment: tile row l%32, K piece 2*kk + l/32 (8 bf16 = 16 bytes)
     const int frow = lane & 31, fhalf = lane >> 5;
-    const int fsw = (frow >> SWS) & 7;
+    const int fsw = (frow >> 1) & 7;
     int rd_a[4], rd_b[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
         const int piece = ((kk << 1) | fhalf) ^ fsw;
         rd_a[kk] = (wm * 128 + frow) * 128 + (piece << 4);
-        rd_b[kk] = FG_TILE_BYTES + (wn * 128 + frow) * 128 + (piece << 4);
+        rd_b[kk] = (wn * 128 + frow) * 128 + (piece << 4);
     }
     // Fragment order a0 b0 b1 b2 b3 a1 a2 a3 = the order the MFMAs below need them.
     bf16x8 fa[2][4], fb[2][4];
-    auto read_frags = [&](int stage, int kk, auto buf) {
+    auto read_frags = [&](int slot_a, int slot_b, int kk, auto buf) {
         constexpr int Bf = decltype(buf)::value;
-        const unsigned char* base = smem + stage * FG_STAGE_BYTES;
-        fa[Bf][0] = *reinterpret_cast<const bf16x8*>(base + rd_a[kk]);
+        const unsigned char* pa = smem + slot_a * FG_TILE_BYTES + rd_a[kk];
+        const unsigned char* pb = smem + slot_b * FG_TILE_BYTES + rd_b[kk];
+        fa[Bf][0] = *reinterpret_cast<const bf16x8*>(pa);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            fb[Bf][j] = *reinterpret_cast<const bf16x8*>(base + rd_b[kk] + j * 4096);
+        for (int j = 0; j < 4; ++j) fb[Bf][j] = *reinterpret_cast<const bf16x8*>(pb + j * 4096);
 #pragma unroll
-        for (int i = 1; i < 4; ++i)
-            fa[Bf][i] = *reinterpret_cast<const bf16x8*>(base + rd_a[kk] + i * 4096);
+        for (int i = 1; i < 4; ++i) fa[Bf][i] = *reinterpret_cast<const bf16x8*>(pa + i * 4096);
     };
 
     f32x16 acc[4][4];
@@ -153,54 +164,63 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_nt_256(FGArgs a) {
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
 
-    // Instruction-mix hints for the backend scheduler.  Per K step a wavefront
-    // issues 64 MFMAs, 32 LDS reads and 16 direct-to-LDS loads; the memory
-    // instructions are spread between the MFMAs instead of issued in bursts.
-    constexpr int SG_MFMA = 0x008, SG_VMEM = 0x010, SG_DS_RD = 0x100;
-#define FG_SLOT(mask)                                        \
-    __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);     \
-    __builtin_amdgcn_sched_group_barrier((mask), 1, 0);
-#define FG_PHASE(n_ld)                                                  \
-    _Pragma("unroll") for (int q_ = 0; q_ < 8; ++q_) {                  \
-        FG_SLOT(SG_DS_RD)                                               \
-        if (q_ < (n_ld)) { FG_SLOT(SG_VMEM) }                           \
-        else { __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0); }   \
-    }
+    // Workgroup barrier of the pipeline.  Loads complete in order and every
+    // wavefront issues 8 per slot, so "at most 8 outstanding" means everything
+    // but the youngest slot (the A tile two steps ahead) has landed.  All LDS
+    // reads of the step are complete as well, so its two slots can be refilled.
+    auto pipeline_barrier = [&]() {
+        asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    };
 
-    // One K step on the tile in LDS stage `cur`; tile t+1 streams into the other
-    // stage meanwhile and has to be complete at the barrier.  A tile beyond the
-    // last one is loaded but never consumed (the descriptor returns zeros past
+    // One K step.  PH = t % 5 fixes the slots: A(t) in (2 PH) % 5, B(t) in
+    // (2 PH + 1) % 5; B(t+1) refills the slot A(t-1) left, A(t+2) the slot B(t-1)
+    // left.  The fourth K=16 sub-step of a tile is multiplied at the start of the
+    // next step, behind the barrier, while the new fragments arrive.  Tiles past
+    // the end are loaded but never consumed (the descriptor returns zeros past
     // its range), which keeps the steady state free of branches.
+    auto step = [&](auto phase, int t) {
+        constexpr int PH = decltype(phase)::value;
+        constexpr int SA = (2 * PH) % 5, SB = (2 * PH + 1) % 5;
+        constexpr int SB1 = (2 * PH + 3) % 5, SA2 = (2 * PH + 4) % 5;
+        read_frags(SA, SB, 0, I0{});
+        gload_b(t + 1, SB1);
+        mma(I1{});                       // sub-step 3 of the previous tile
+        read_frags(SA, SB, 1, I1{});
+        gload_a(t + 2, SA2);
+        mma(I0{});
+        read_frags(SA, SB, 2, I0{});
+        mma(I1{});
+        read_frags(SA, SB, 3, I1{});
+        mma(I0{});
+        pipeline_barrier();
+    };
+
     const int nk = a.K / FG_BK;
-    gload(0, 0, 0, 16);
-    __syncthreads();
-    read_frags(0, 0, I0{});
-    gload(1, 1, 0, 8);
-    for (int t = 0; t < nk; ++t) {
-        const int cur = t & 1, nxt = cur ^ 1;
-        // K sub-step 0 (fragments of sub-step 1 arrive meanwhile)
-        read_frags(cur, 1, I1{});
-        gload(nxt, t + 1, 8, 16);
-        mma(I0{});
-        // K sub-step 1
-        read_frags(cur, 2, I0{});
-        mma(I1{});
-        // K sub-step 2
-        read_frags(cur, 3, I1{});
-        mma(I0{});
-        FG_PHASE(8)
-        FG_PHASE(0)
-        FG_PHASE(0)
-        __syncthreads();   // stage nxt complete (loads drained), stage cur read by everyone
-        // K sub-step 3 runs on fragments already in registers while the first
-        // fragments of the next stage arrive and the loads of tile t+2 start
-        read_frags(nxt, 0, I0{});
-        gload(cur, t + 2, 0, 8);
-        mma(I1{});
-        FG_PHASE(8)
+    gload_a(0, 0);
+    gload_b(0, 1);
+    gload_a(1, 2);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {        // the first step has no previous sub-step: add zero
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            fa[1][i][e] = (bf16_t)0.f;
+            fb[1][i][e] = (bf16_t)0.f;
+        }
     }
-#undef FG_PHASE
-#undef FG_SLOT
+    pipeline_barrier();
+    int t = 0;
+    for (; t + 5 <= nk; t += 5) {
+        step(std::integral_constant<int, 0>{}, t);
+        step(std::integral_constant<int, 1>{}, t + 1);
+        step(std::integral_constant<int, 2>{}, t + 2);
+        step(std::integral_constant<int, 3>{}, t + 3);
+        step(std::integral_constant<int, 4>{}, t + 4);
+    }
+    if (t < nk) step(std::integral_constant<int, 0>{}, t++);
+    if (t < nk) step(std::integral_constant<int, 1>{}, t++);
+    if (t < nk) step(std::integral_constant<int, 2>{}, t++);
+    if (t < nk) step(std::integral_constant<int, 3>{}, t++);
+    mma(I1{});
     // the loads of the tiles past the end still target LDS: let them land before
     // the workgroup can retire and its LDS be handed to another one
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
