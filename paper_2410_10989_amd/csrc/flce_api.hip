@@ -125,40 +125,22 @@ int launch_gemm_generic(int kind, const T* A, int64_t lda, const T* B, int64_t l
     return FLCE_OK;
 }
 
-// Tuned bf16 kernel when the operands allow it, the guarded kernel otherwise.
-template <typename T, typename OutT>
-int launch_gemm(int kind, const T* A, int64_t lda, const T* B, int64_t ldb, OutT* C, int64_t ldc,
-                int64_t M, int64_t N, int64_t K, bool accum, hipStream_t s) {
-    if (M <= 0 || N <= 0) return FLCE_OK;
-    if constexpr (sizeof(T) == 2) {
-        const int64_t ld_max = lda > ldb ? lda : ldb;
-        const bool fast = (K > 0) && (K % FG_BK == 0) && (lda % 8 == 0) && (ldb % 8 == 0) &&
-                          aligned(A, 16) && aligned(B, 16) &&
-                          ((FG_BM * ld_max + K + 256) * 2 < ((int64_t)1 << 31)) &&
-                          (FG_BM * ldc * (int64_t)sizeof(OutT) < ((int64_t)1 << 31));
-        // accumulation only ever targets the fp32 dW scratch
-        if (fast && (!accum || sizeof(OutT) == 4)) {
-            ScopedKernelTimer timer(kind, s);
-            FGArgs a{A, lda, B, ldb, C, ldc, (int)M, (int)N, (int)K,
-                     (int)((M + FG_BM - 1) / FG_BM), (int)((N + FG_BN - 1) / FG_BN)};
-            const int64_t total = (int64_t)a.tiles_m * a.tiles_n;
-            const dim3 grid((unsigned)((total + FG_XCDS - 1) / FG_XCDS * FG_XCDS));
-            if constexpr (sizeof(OutT) == 4) {
-                if (accum) {
-                    hipLaunchKernelGGL((gemm_bf16_nt_256<OutT, true>), grid, dim3(FG_THREADS), 0, s,
-                                       a);
-                    HIP_TRY(hipGetLastError());
-                    return FLCE_OK;
-                }
-            }
-            {
-                hipLaunchKernelGGL((gemm_bf16_nt_256<OutT, false>), grid, dim3(FG_THREADS), 0, s, a);
-            }
-            HIP_TRY(hipGetLastError());
-            return FLCE_OK;
-        }
-    }
-    return launch_gemm_generic<T, OutT>(kind, A, lda, B, ldb, C, ldc, M, N, K, accum, s);
+// Tuned bf16 kernel (see gemm_bf16_nt.h for what A_KM / B_KM / HAS_IN mean).  The
+// caller has checked the shape limits (Plan::fast_*).
+template <typename OutT, bool HAS_IN, bool A_KM, bool B_KM>
+int launch_gemm_fast(int kind, const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, OutT* C,
+                     int64_t ldc, const float* Cin, int64_t ldcin, int64_t M, int64_t N, int64_t K,
+                     hipStream_t s) {
+    if (M <= 0 || N <= 0 || K <= 0) return FLCE_OK;
+    if (K % FG_BK != 0 || !aligned(A, 16) || !aligned(B, 16)) return FLCE_ERR_ARG;
+    ScopedKernelTimer timer(kind, s);
+    FGArgs a{A, lda, B, ldb, C, ldc, Cin, ldcin, (int)M, (int)N, (int)K,
+             (int)((M + FG_BM - 1) / FG_BM), (int)((N + FG_BN - 1) / FG_BN)};
+    const int64_t total = (int64_t)a.tiles_m * a.tiles_n;
+    const dim3 grid((unsigned)((total + FG_XCDS - 1) / FG_XCDS * FG_XCDS));
+    hipLaunchKernelGGL((gemm_bf16_256<OutT, HAS_IN, A_KM, B_KM>), grid, dim3(FG_THREADS), 0, s, a);
+    HIP_TRY(hipGetLastError());
+    return FLCE_OK;
 }
 
 template <typename T>
@@ -201,6 +183,7 @@ template <typename T>
 int run_fwd_bwd(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t H, int64_t V,
                 int64_t ignore_index, float* loss, T* dX, T* dW, unsigned flags, const Plan& p,
                 char* ws, hipStream_t s) {
+    constexpr bool BF16 = (sizeof(T) == 2);
     const bool want_dx = !(flags & FLCE_SKIP_DX), want_dw = !(flags & FLCE_SKIP_DW);
     DeviceHeader* hdr = reinterpret_cast<DeviceHeader*>(ws + p.off_hdr);
     float* row_loss = reinterpret_cast<float*>(ws + p.off_row_loss);
@@ -213,36 +196,77 @@ int run_fwd_bwd(const T* X, const T* W, const int64_t* targets, int64_t BT, int6
     hipLaunchKernelGGL(count_valid_kernel, dim3(1), dim3(1024), 0, s, targets, BT, ignore_index,
                        hdr);
     HIP_TRY(hipGetLastError());
-    if (want_dx) FLCE_TRY(launch_transpose<T>(W, H, WT, p.ldz, V, H, s));   // WT[H x V]
+    if (want_dx && !p.fast_dx) FLCE_TRY(launch_transpose<T>(W, H, WT, p.ldz, V, H, s));   // WT[H x V]
 
+    bool dw_needs_cast = false;
     for (int64_t c = 0; c < p.nchunks; ++c) {
         const int64_t r0 = c * p.C;
         const int64_t rows = (BT - r0 < p.C) ? BT - r0 : p.C;
+        const bool last = (c == p.nchunks - 1);
         const T* Xc = X + r0 * H;
+
         // logits of the chunk: Z = X_c W^T
-        FLCE_TRY((launch_gemm<T, T>(FLCE_KIND_LOGITS_GEMM, Xc, H, W, H, Z, p.ldz, rows, V, H, false, s)));
+        if (BF16 && p.fast_logits) {
+            if constexpr (BF16)
+                FLCE_TRY((launch_gemm_fast<bf16_t, false, false, false>(
+                    FLCE_KIND_LOGITS_GEMM, Xc, H, W, H, Z, p.ldz, nullptr, 0, rows, V, H, s)));
+        } else {
+            FLCE_TRY((launch_gemm_generic<T, T>(FLCE_KIND_LOGITS_GEMM, Xc, H, W, H, Z, p.ldz, rows, V, H,
+                                                false, s)));
+        }
+
         // loss and in-place dlogits
         FLCE_TRY(launch_ce_rows<T>(Z, p.ldz, targets + r0, rows, V, ignore_index, hdr, row_loss, s));
-        // dX_c = G W  (as G [rows x V] times WT[H x V]^T)
-        if (want_dx)
-            FLCE_TRY((launch_gemm<T, T>(FLCE_KIND_DX_GEMM, Z, p.ldz, WT, p.ldz, dX + r0 * H, H, rows, H, V,
-                                                false, s)));
-        // dW (+)= G^T X_c  (as GT[V x rows] times XT[H x rows]^T)
-        if (want_dw) {
-            FLCE_TRY(launch_transpose<T>(Z, p.ldz, GT, p.ldc, rows, V, s));
-            FLCE_TRY(launch_transpose<T>(Xc, H, XT, p.ldc, rows, H, s));
-            if (p.fp32_dw_acc) {
-                FLCE_TRY((launch_gemm<T, float>(FLCE_KIND_DW_GEMM, GT, p.ldc, XT, p.ldc, dWacc, H, V, H, rows,
-                                                        c > 0, s)));
+
+        // dX_c = G W
+        if (want_dx) {
+            if (BF16 && p.fast_dx) {
+                if constexpr (BF16)
+                    FLCE_TRY((launch_gemm_fast<bf16_t, false, false, true>(
+                        FLCE_KIND_DX_GEMM, Z, p.ldz, W, H, dX + r0 * H, H, nullptr, 0, rows, H, V, s)));
             } else {
-                FLCE_TRY((launch_gemm<T, T>(FLCE_KIND_DW_GEMM, GT, p.ldc, XT, p.ldc, dW, H, V, H, rows, c > 0,
-                                                    s)));
+                FLCE_TRY((launch_gemm_generic<T, T>(FLCE_KIND_DX_GEMM, Z, p.ldz, WT, p.ldz, dX + r0 * H,
+                                                    H, rows, H, V, false, s)));
+            }
+        }
+
+        // dW (+)= G^T X_c
+        if (want_dw) {
+            const bool fast = BF16 && (last ? p.fast_dw_last : p.fast_dw_full);
+            if (fast) {
+                if constexpr (BF16) {
+                    if (p.nchunks == 1) {
+                        FLCE_TRY((launch_gemm_fast<bf16_t, false, true, true>(
+                            FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dW, H, nullptr, 0, V, H, rows, s)));
+                    } else if (c == 0) {
+                        FLCE_TRY((launch_gemm_fast<float, false, true, true>(
+                            FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dWacc, H, nullptr, 0, V, H, rows, s)));
+                    } else if (!last) {
+                        FLCE_TRY((launch_gemm_fast<float, true, true, true>(
+                            FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dWacc, H, dWacc, H, V, H, rows, s)));
+                    } else {   // last chunk: add the fp32 partial sums and write dW in bf16
+                        FLCE_TRY((launch_gemm_fast<bf16_t, true, true, true>(
+                            FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dW, H, dWacc, H, V, H, rows, s)));
+                    }
+                }
+            } else {
+                // guarded path: GT[V x rows] times XT[H x rows]^T
+                FLCE_TRY(launch_transpose<T>(Z, p.ldz, GT, p.ldc, rows, V, s));
+                FLCE_TRY(launch_transpose<T>(Xc, H, XT, p.ldc, rows, H, s));
+                if (p.fp32_dw_acc) {
+                    FLCE_TRY((launch_gemm_generic<T, float>(FLCE_KIND_DW_GEMM, GT, p.ldc, XT, p.ldc,
+                                                            dWacc, H, V, H, rows, c > 0, s)));
+                    dw_needs_cast = last;
+                } else {
+                    FLCE_TRY((launch_gemm_generic<T, T>(FLCE_KIND_DW_GEMM, GT, p.ldc, XT, p.ldc, dW, H,
+                                                        V, H, rows, c > 0, s)));
+                }
             }
         }
     }
     hipLaunchKernelGGL(finalize_loss_kernel, dim3(1), dim3(64), 0, s, hdr, loss);
     HIP_TRY(hipGetLastError());
-    if (want_dw && p.fp32_dw_acc) {
+    if (want_dw && dw_needs_cast) {
         ScopedKernelTimer timer(FLCE_KIND_OTHER, s);
         hipLaunchKernelGGL((cast_from_f32_kernel<T>), dim3(2048), dim3(256), 0, s, dWacc, dW,
                            V * H);

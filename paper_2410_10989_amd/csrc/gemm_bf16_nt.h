@@ -1,7 +1,12 @@
-// Tuned bf16 "NT" matrix product for gfx950:
-//     C[M x N] (+)= A[M x K] * B[N x K]^T     (A, B row-major bf16, K contiguous)
-// fp32 accumulation on v_mfma_f32_32x32x16_bf16.  All three products of the
-// fused linear cross-entropy path (logits, dX, dW) are brought into this form.
+// Tuned bf16 matrix product for gfx950, fp32 accumulation on
+// v_mfma_f32_32x32x16_bf16:
+//     C[M x N] = (Cin +) sum_k a(m,k) * b(n,k)
+// where each operand is given either K-contiguous ("row" form: a(m,k) = A[m*lda + k])
+// or K-major ("column" form: a(m,k) = A[k*lda + m]).  All three products of the
+// fused linear cross-entropy path run on it without transposed copies:
+//     logits  Z  = X_c W^T      A = X_c row form,  B = W   row form
+//     dX_c       = G W          A = G   row form,  B = W   column form (K = V)
+//     dW        += G^T X_c      A = G   column form, B = X_c column form (K = chunk rows)
 //
 // Shape of the kernel
 //  - workgroup = 256 threads = 4 wavefronts (2 x 2); macro tile 256 x 256, K step
@@ -9,28 +14,40 @@
 //    accumulator registers per lane (one wavefront per SIMD, full register file).
 //  - global -> LDS directly (buffer_load_dwordx4 ... lds): no vector registers
 //    and no LDS write instructions are spent on staging.  The buffer descriptor's
-//    byte range makes rows beyond M / N read as zero and keeps offsets 32-bit.
+//    byte range makes reads past the operand return zero and keeps offsets 32-bit.
 //  - the whole 160 KB LDS of the CU is a ring of five 32 KB slots, each holding
-//    the A tile or the B tile (256 rows x 64 bf16) of one K step, filled in the
-//    order A0 B0 A1 B1 A2 ...  While step t is multiplied, B(t+1) and A(t+2)
-//    stream in, so the loads run up to two steps ahead and the memory pipe is
-//    fed continuously instead of in one burst per step; one workgroup barrier
-//    per K step, which waits for all but the youngest slot (s_waitcnt vmcnt(8)).
-//    What limits this kernel next to the matrix pipe is L2 bandwidth: a 256 x 256
-//    tile needs 128 B per row and step from L2, 16 TB/s at 2 PFLOP/s.
-//  - LDS rows are 128 B (64 bf16); the eight 16-byte pieces of a row are XOR
-//    swizzled with (row / 2) % 8 so that ds_read_b128 of one K piece over
+//    the A tile or the B tile of one K step, filled in the order A0 B0 A1 B1 A2 ...
+//    While step t is multiplied, B(t+1) and A(t+2) stream in, so the loads run up
+//    to two steps ahead and the memory pipe is fed continuously; one workgroup
+//    barrier per K step, which waits for all but the youngest slot
+//    (s_waitcnt vmcnt(8)).  Next to the matrix pipe the limit is L2 bandwidth:
+//    a 256 x 256 tile pulls 64 KB per K step from L2, 16 TB/s at 2 PFLOP/s.
+//  - row-form tiles sit in LDS as 256 rows of 128 B whose eight 16-byte pieces are
+//    XOR swizzled with (row / 2) % 8, so that ds_read_b128 of one K piece over
 //    consecutive rows (the MFMA operand pattern) spreads over all banks.
+//  - column-form tiles sit in LDS as 64 K rows of 512 B (the layout they have in
+//    memory) whose eight 64-byte chunks are XOR swizzled with a function of the K
+//    row; fragments are fetched with ds_read_b64_tr_b16, the transposing LDS read:
+//    inside each group of 16 lanes it turns 4 K rows x 16 columns into 16 lanes x
+//    4 consecutive K values, which is the MFMA operand layout.
 //  - operand fragments are double buffered in registers across the four K=16
 //    sub-steps; the last sub-step of a tile runs behind the barrier while the
-//    first fragments of the next tile arrive.
+//    first fragments of the next tile arrive.  The LDS reads are issued as inline
+//    assembly with explicit s_waitcnt: the compiler would otherwise put a full
+//    vmcnt(0) in front of every transposing read (it cannot tell that the read
+//    does not alias an in-flight direct-to-LDS load), and it clusters reads
+//    instead of issuing one per MFMA.  The instruction order of the steady state
+//    is pinned with sched_barrier: MFMA, LDS read(s) or one load, MFMA, ...
 //  - workgroup id -> tile: ids are dealt round-robin to the 8 XCDs, so id%8
 //    selects the XCD and each XCD walks its own contiguous span of a grouped
 //    (8 tile rows at a time) tile order; tiles that run together on one XCD
 //    share A and B panels in that XCD's L2.
-// Requirements (checked on the host): K % 64 == 0, lda % 8 == 0, ldb % 8 == 0,
-// A and B 16-byte aligned, (256 * ld + K + 256) * 2 bytes < 2^31 for lda and ldb,
-// 256 * ldc * sizeof(C element) < 2^31.  M and N are arbitrary.
+// Requirements (checked on the host): K % 64 == 0, leading dimensions % 8 == 0,
+// A and B 16-byte aligned, every byte offset inside an operand tile below 2^31
+// (row form: (256 * ld + K + 256) * 2; column form: (K + 192) * ld * 2),
+// 256 * ldc * sizeof(element) < 2^31 for C and Cin.  M and N are arbitrary:
+// tile rows / columns past them hold zeros or stale values and only feed outputs
+// that are never stored.
 #pragma once
 #include <type_traits>
 
@@ -52,17 +69,150 @@ struct FGArgs {
     int64_t ldb;
     void* C;
     int64_t ldc;
+    const float* Cin;   // optional fp32 addend (may alias C when C is fp32)
+    int64_t ldcin;
     int M, N, K;
     int tiles_m, tiles_n;
 };
 
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) void* fg_lds_ptr;
+
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t fg_make_rsrc(const void* base, uint32_t bytes) {
-    // raw buffer, no stride: offsets >= bytes read as zero
+    // raw buffer, no stride: offsets >= bytes read as zero / are not written
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
 
-template <typename OutT, bool ACCUM>
-__global__ __launch_bounds__(FG_THREADS) void gemm_bf16_nt_256(FGArgs a) {
+// One GEMM operand: where its tiles come from in global memory, where they land
+// in LDS, and how MFMA fragments (32 rows x 16 K, lane l = row l%32, K values
+// 8*(l/32) .. +7) are read back.  KM = false: row form, KM = true: column form.
+template <bool KM>
+struct FgOperand {
+    __amdgpu_buffer_rsrc_t rsrc;
+    int off[8];   // per-lane byte offset of each of the 8 loads a wavefront issues per tile
+    int kstep;    // bytes between consecutive K steps
+    int rd[4];    // per-lane LDS byte offsets of the fragment reads
+
+    // base/ld: the matrix; r0: first row (row form) or column (column form) of this
+    // tile; extent: number of rows / columns of the matrix; sub: which 128-wide half
+    // of the tile this wavefront multiplies.
+    __device__ __forceinline__ void init(const bf16_t* base, int64_t ld, int r0, int extent, int K,
+                                         int tid, int sub) {
+        const int lane = tid & 63, wave = tid >> 6;
+        const int ildb = (int)ld * 2;   // leading dimension in bytes
+        if constexpr (!KM) {
+            // a wavefront-wide load = 8 consecutive tile rows of 128 B; lane l owns the
+            // physical position (row l/8, piece l%8) and fetches the logical piece
+            // (l%8) ^ swizzle(row); wavefront w fills rows 8w..8w+7 of every 32-row group
+            const int rows = min(FG_BM, extent - r0);
+            rsrc = fg_make_rsrc(base + (int64_t)r0 * ld, (uint32_t)rows * (uint32_t)ildb);
+            const int ld_row = tid >> 3;
+            const int piece = (tid & 7) ^ ((ld_row >> 1) & 7);
+#pragma unroll
+            for (int r = 0; r < 8; ++r) off[r] = (ld_row + 32 * r) * ildb + piece * 16;
+            kstep = FG_BK * 2;
+            const int frow = lane & 31, fhalf = lane >> 5, fsw = (frow >> 1) & 7;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                rd[kk] = (sub * 128 + frow) * 128 + ((((kk << 1) | fhalf) ^ fsw) << 4);
+        } else {
+            // a wavefront-wide load = 2 consecutive K rows of 512 B; load r of wavefront
+            // w covers K rows 8r + 2w and 8r + 2w + 1; lane l owns the physical 16-byte
+            // piece l%32 of row l/32 and fetches the logical 64-byte chunk
+            // (piece / 4) ^ f(k), f(k) = k%4 + 4 * ((k/8) % 2)
+            rsrc = fg_make_rsrc(base + r0, ((uint32_t)K * (uint32_t)ld - (uint32_t)r0) * 2u);
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const int k = 8 * r + 2 * wave + (lane >> 5);
+                const int f = (k & 3) | (((k >> 3) & 1) << 2);
+                const int chunk = ((lane & 31) >> 2) ^ f;
+                off[r] = k * ildb + chunk * 64 + (lane & 3) * 16;
+            }
+            kstep = FG_BK * ildb;
+            // transposing read: group g = l/16 of the wavefront reads K rows
+            // 8*(g/2) + {0..3} (+4 for the second read), columns 16*(g%2) + 0..15 of the
+            // 32-wide fragment; source lane s = l%16 supplies row s/4, columns 4*(s%4)..+3
+            const int g = lane >> 4, s = lane & 15;
+            const int f = (s >> 2) | ((g >> 1) << 2);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                rd[i] = (8 * (g >> 1) + (s >> 2)) * 512 + (((sub * 4 + i) ^ f) * 64) + 32 * (g & 1) +
+                        8 * (s & 3);
+        }
+    }
+
+    // start the 8 loads of this wavefront for K step kt into ring slot `slot`
+    __device__ __forceinline__ void load(unsigned char* smem, int slot, int kt, int uwave) const {
+        const int soff = kt * kstep;
+        unsigned char* dst = smem + slot * FG_TILE_BYTES + uwave * 1024;
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (fg_lds_ptr)(dst + r * 4096), 16, off[r], soff,
+                                                     0, 0);
+    }
+
+    // start one of the 8 loads of this wavefront for K step kt into ring slot `slot`
+    __device__ __forceinline__ void load_one(unsigned char* smem, int slot, int kt, int uwave, int r) const {
+        unsigned char* dst = smem + slot * FG_TILE_BYTES + uwave * 1024 + r * 4096;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (fg_lds_ptr)dst, 16, off[r], kt * kstep, 0, 0);
+    }
+};
+
+// Registers an in-flight fragment lands in.  The reads are asynchronous inline
+// assembly: nothing may touch these registers until fg_wait has run.
+template <bool KM> struct FgRaw;
+template <> struct FgRaw<false> { bf16x8 v; };
+template <> struct FgRaw<true> { s16x4 lo, hi; };
+
+// Issue the LDS read(s) of fragment I (32-row block) of K sub-step KK; `slot_addr`
+// is the LDS byte address of the ring slot.
+template <int KK, int I>
+__device__ __forceinline__ void fg_issue(FgRaw<false>& r, const FgOperand<false>& op, unsigned slot_addr) {
+    const unsigned addr = slot_addr + (unsigned)op.rd[KK];
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r.v) : "v"(addr), "n"(I * 4096));
+}
+template <int KK, int I>
+__device__ __forceinline__ void fg_issue(FgRaw<true>& r, const FgOperand<true>& op, unsigned slot_addr) {
+    const unsigned addr = slot_addr + (unsigned)op.rd[I];
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r.lo) : "v"(addr), "n"(KK * 8192));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r.hi) : "v"(addr), "n"(KK * 8192 + 2048));
+}
+
+// Wait until every LDS read issued so far has returned.  The registers are tied
+// to the asm statements so that nothing that uses them is moved above the wait.
+__device__ __forceinline__ void fg_tie(FgRaw<false> (&r)[4]) {
+    asm volatile("" : "+v"(r[0].v), "+v"(r[1].v), "+v"(r[2].v), "+v"(r[3].v));
+}
+__device__ __forceinline__ void fg_tie(FgRaw<true> (&r)[4]) {
+    asm volatile("" : "+v"(r[0].lo), "+v"(r[0].hi), "+v"(r[1].lo), "+v"(r[1].hi), "+v"(r[2].lo),
+                 "+v"(r[2].hi), "+v"(r[3].lo), "+v"(r[3].hi));
+}
+template <bool AKM, bool BKM>
+__device__ __forceinline__ void fg_wait(FgRaw<AKM> (&ra)[4], FgRaw<BKM> (&rb)[4]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    fg_tie(ra);
+    fg_tie(rb);
+}
+__device__ __forceinline__ bf16x8 fg_value(const FgRaw<false>& r) { return r.v; }
+__device__ __forceinline__ bf16x8 fg_value(const FgRaw<true>& r) {
+    const s16x8 both = __builtin_shufflevector(r.lo, r.hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, both);
+}
+__device__ __forceinline__ void fg_zero(FgRaw<false>& r) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r.v[e] = (bf16_t)0.f;
+}
+__device__ __forceinline__ void fg_zero(FgRaw<true>& r) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        r.lo[e] = 0;
+        r.hi[e] = 0;
+    }
+}
+
+template <typename OutT, bool HAS_IN, bool A_KM, bool B_KM>
+__global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
     __shared__ __attribute__((aligned(16))) unsigned char smem[FG_LDS_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -81,69 +231,13 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_nt_256(FGArgs a) {
     const int pm = first_m + rem % gm, pn = rem / gm;
     const int m0 = pm * FG_BM, n0 = pn * FG_BN;
 
-    // ---- global side: direct-to-LDS buffer loads ----
-    // One wavefront-wide load moves 64 x 16 bytes straight into LDS at
-    // M0 + lane * 16, i.e. 8 consecutive tile rows of 128 bytes.  Lane l therefore
-    // owns the physical position (row l/8, piece l%8) and fetches the logical
-    // piece (l%8) ^ swizzle(row) from global memory.  Wavefront w fills rows
-    // 8w..8w+7 of every 32-row group; 8 loads per operand per K step.
-    const int rows_a = min(FG_BM, a.M - m0), rows_b = min(FG_BN, a.N - n0);
-    const __amdgpu_buffer_rsrc_t rsrc_a =
-        fg_make_rsrc(a.A + (int64_t)m0 * a.lda, (uint32_t)rows_a * (uint32_t)a.lda * 2u);
-    const __amdgpu_buffer_rsrc_t rsrc_b =
-        fg_make_rsrc(a.B + (int64_t)n0 * a.ldb, (uint32_t)rows_b * (uint32_t)a.ldb * 2u);
-    const int ld_row = tid >> 3;                                   // 0..31
-    const int ld_piece = (tid & 7) ^ ((ld_row >> 1) & 7);        // logical piece fetched
-    int off_a[8], off_b[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        off_a[i] = (ld_row + 32 * i) * (int)a.lda * 2 + ld_piece * 16;
-        off_b[i] = (ld_row + 32 * i) * (int)a.ldb * 2 + ld_piece * 16;
-    }
+    FgOperand<A_KM> opa;
+    FgOperand<B_KM> opb;
+    opa.init(a.A, a.lda, m0, a.M, a.K, tid, wm);
+    opb.init(a.B, a.ldb, n0, a.N, a.K, tid, wn);
     const int uwave = __builtin_amdgcn_readfirstlane(wave);
-    typedef __attribute__((address_space(3))) void* lds_ptr_t;
-    // The ring: operand tiles are loaded in the order A0 B0 A1 B1 A2 ... and item
-    // number n lives in slot n % 5.  8 loads per wavefront fill one slot.
-    auto gload_a = [&](int kt, int slot) {
-        const int soff = kt * (FG_BK * 2);
-        unsigned char* dst = smem + slot * FG_TILE_BYTES + uwave * 1024;
-#pragma unroll
-        for (int r = 0; r < 8; ++r)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lds_ptr_t)(dst + r * 4096), 16, off_a[r],
-                                                     soff, 0, 0);
-    };
-    auto gload_b = [&](int kt, int slot) {
-        const int soff = kt * (FG_BK * 2);
-        unsigned char* dst = smem + slot * FG_TILE_BYTES + uwave * 1024;
-#pragma unroll
-        for (int r = 0; r < 8; ++r)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lds_ptr_t)(dst + r * 4096), 16, off_b[r],
-                                                     soff, 0, 0);
-    };
 
-    // ---- LDS side: MFMA operand fragments ----
-    // lane l of a fragment: tile row l%32, K piece 2*kk + l/32 (8 bf16 = 16 bytes)
-    const int frow = lane & 31, fhalf = lane >> 5;
-    const int fsw = (frow >> 1) & 7;
-    int rd_a[4], rd_b[4];
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        const int piece = ((kk << 1) | fhalf) ^ fsw;
-        rd_a[kk] = (wm * 128 + frow) * 128 + (piece << 4);
-        rd_b[kk] = (wn * 128 + frow) * 128 + (piece << 4);
-    }
-    // Fragment order a0 b0 b1 b2 b3 a1 a2 a3 = the order the MFMAs below need them.
-    bf16x8 fa[2][4], fb[2][4];
-    auto read_frags = [&](int slot_a, int slot_b, int kk, auto buf) {
-        constexpr int Bf = decltype(buf)::value;
-        const unsigned char* pa = smem + slot_a * FG_TILE_BYTES + rd_a[kk];
-        const unsigned char* pb = smem + slot_b * FG_TILE_BYTES + rd_b[kk];
-        fa[Bf][0] = *reinterpret_cast<const bf16x8*>(pa);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) fb[Bf][j] = *reinterpret_cast<const bf16x8*>(pb + j * 4096);
-#pragma unroll
-        for (int i = 1; i < 4; ++i) fa[Bf][i] = *reinterpret_cast<const bf16x8*>(pa + i * 4096);
-    };
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -152,17 +246,10 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_nt_256(FGArgs a) {
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int g = 0; g < 16; ++g) acc[i][j][g] = 0.f;
-    auto mma = [&](auto buf) {
-        constexpr int Bf = decltype(buf)::value;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[Bf][i], fb[Bf][j], acc[i][j],
-                                                                    0, 0, 0);
-    };
-    using I0 = std::integral_constant<int, 0>;
-    using I1 = std::integral_constant<int, 1>;
+
+    // two register buffers of in-flight fragments (4 of A, 4 of B each)
+    FgRaw<A_KM> raw_a[2][4];
+    FgRaw<B_KM> raw_b[2][4];
 
     // Workgroup barrier of the pipeline.  Loads complete in order and every
     // wavefront issues 8 per slot, so "at most 8 outstanding" means everything
@@ -172,40 +259,82 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_nt_256(FGArgs a) {
         asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
     };
 
+    // One quarter of a K step: the 16 MFMAs of one K=16 sub-step on the fragments in
+    // register buffer MB, interleaved with the 8 fragment reads of sub-step KK of the
+    // tile in slots (SA, SB) into buffer 1-MB (one fragment per MFMA, in the order
+    // a0 b0 b1 b2 b3 a1 a2 a3 in which the next quarter consumes them), and with the 8
+    // loads of one operand tile (DMA = 1: B tile of step kt into slot SD, DMA = 2: A
+    // tile) behind the last 8 MFMAs.
+    auto quarter = [&](auto mb_, auto kk_, auto sa_, auto sb_, auto dma_, auto sd_, int kt) {
+        constexpr int MB = decltype(mb_)::value, RB = 1 - MB, KK = decltype(kk_)::value;
+        constexpr int SA = decltype(sa_)::value, SB = decltype(sb_)::value;
+        constexpr int DMA = decltype(dma_)::value, SD = decltype(sd_)::value;
+        fg_wait(raw_a[MB], raw_b[MB]);
+        bf16x8 fa[4], fb[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            fa[i] = fg_value(raw_a[MB][i]);
+            fb[i] = fg_value(raw_b[MB][i]);
+        }
+        const unsigned sa_addr = lds0 + SA * FG_TILE_BYTES, sb_addr = lds0 + SB * FG_TILE_BYTES;
+        __builtin_amdgcn_sched_barrier(0);
+#define FG_MFMA(q) \
+        acc[(q) >> 2][(q) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[(q) >> 2], fb[(q) & 3], acc[(q) >> 2][(q) & 3], 0, 0, 0)
+#define FG_DMA(q)                                                              \
+        if constexpr (DMA == 1) opb.load_one(smem, SD, kt, uwave, (q) - 8);    \
+        if constexpr (DMA == 2) opa.load_one(smem, SD, kt, uwave, (q) - 8);    \
+        __builtin_amdgcn_sched_barrier(0)
+        FG_MFMA(0);  fg_issue<KK, 0>(raw_a[RB][0], opa, sa_addr); __builtin_amdgcn_sched_barrier(0);
+        FG_MFMA(1);  fg_issue<KK, 0>(raw_b[RB][0], opb, sb_addr); __builtin_amdgcn_sched_barrier(0);
+        FG_MFMA(2);  fg_issue<KK, 1>(raw_b[RB][1], opb, sb_addr); __builtin_amdgcn_sched_barrier(0);
+        FG_MFMA(3);  fg_issue<KK, 2>(raw_b[RB][2], opb, sb_addr); __builtin_amdgcn_sched_barrier(0);
+        FG_MFMA(4);  fg_issue<KK, 3>(raw_b[RB][3], opb, sb_addr); __builtin_amdgcn_sched_barrier(0);
+        FG_MFMA(5);  fg_issue<KK, 1>(raw_a[RB][1], opa, sa_addr); __builtin_amdgcn_sched_barrier(0);
+        FG_MFMA(6);  fg_issue<KK, 2>(raw_a[RB][2], opa, sa_addr); __builtin_amdgcn_sched_barrier(0);
+        FG_MFMA(7);  fg_issue<KK, 3>(raw_a[RB][3], opa, sa_addr); __builtin_amdgcn_sched_barrier(0);
+        FG_MFMA(8);  FG_DMA(8);
+        FG_MFMA(9);  FG_DMA(9);
+        FG_MFMA(10); FG_DMA(10);
+        FG_MFMA(11); FG_DMA(11);
+        FG_MFMA(12); FG_DMA(12);
+        FG_MFMA(13); FG_DMA(13);
+        FG_MFMA(14); FG_DMA(14);
+        FG_MFMA(15); FG_DMA(15);
+#undef FG_MFMA
+#undef FG_DMA
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>;
+
     // One K step.  PH = t % 5 fixes the slots: A(t) in (2 PH) % 5, B(t) in
     // (2 PH + 1) % 5; B(t+1) refills the slot A(t-1) left, A(t+2) the slot B(t-1)
-    // left.  The fourth K=16 sub-step of a tile is multiplied at the start of the
-    // next step, behind the barrier, while the new fragments arrive.  Tiles past
-    // the end are loaded but never consumed (the descriptor returns zeros past
-    // its range), which keeps the steady state free of branches.
+    // left.  The fourth K=16 sub-step of a tile is multiplied in the first quarter
+    // of the next step, behind the barrier, while the new fragments arrive.  Tiles
+    // past the end are loaded but never consumed (the descriptor returns zeros
+    // past its range), which keeps the steady state free of branches.
     auto step = [&](auto phase, int t) {
         constexpr int PH = decltype(phase)::value;
-        constexpr int SA = (2 * PH) % 5, SB = (2 * PH + 1) % 5;
-        constexpr int SB1 = (2 * PH + 3) % 5, SA2 = (2 * PH + 4) % 5;
-        read_frags(SA, SB, 0, I0{});
-        gload_b(t + 1, SB1);
-        mma(I1{});                       // sub-step 3 of the previous tile
-        read_frags(SA, SB, 1, I1{});
-        gload_a(t + 2, SA2);
-        mma(I0{});
-        read_frags(SA, SB, 2, I0{});
-        mma(I1{});
-        read_frags(SA, SB, 3, I1{});
-        mma(I0{});
+        using SA = std::integral_constant<int, (2 * PH) % 5>;
+        using SB = std::integral_constant<int, (2 * PH + 1) % 5>;
+        using SB1 = std::integral_constant<int, (2 * PH + 3) % 5>;
+        using SA2 = std::integral_constant<int, (2 * PH + 4) % 5>;
+        quarter(I1{}, I0{}, SA{}, SB{}, I1{}, SB1{}, t + 1);   // MFMA: sub-step 3 of tile t-1
+        quarter(I0{}, I1{}, SA{}, SB{}, I2{}, SA2{}, t + 2);   // MFMA: sub-step 0
+        quarter(I1{}, I2{}, SA{}, SB{}, I0{}, I0{}, 0);        // MFMA: sub-step 1
+        quarter(I0{}, I3{}, SA{}, SB{}, I0{}, I0{}, 0);        // MFMA: sub-step 2
         pipeline_barrier();
     };
 
     const int nk = a.K / FG_BK;
-    gload_a(0, 0);
-    gload_b(0, 1);
-    gload_a(1, 2);
+    opa.load(smem, 0, 0, uwave);
+    opb.load(smem, 1, 0, uwave);
+    opa.load(smem, 2, 1, uwave);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {        // the first step has no previous sub-step: add zero
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            fa[1][i][e] = (bf16_t)0.f;
-            fb[1][i][e] = (bf16_t)0.f;
-        }
+        fg_zero(raw_a[1][i]);
+        fg_zero(raw_b[1][i]);
     }
     pipeline_barrier();
     int t = 0;
@@ -220,22 +349,37 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_nt_256(FGArgs a) {
     if (t < nk) step(std::integral_constant<int, 1>{}, t++);
     if (t < nk) step(std::integral_constant<int, 2>{}, t++);
     if (t < nk) step(std::integral_constant<int, 3>{}, t++);
-    mma(I1{});
+    {   // sub-step 3 of the last tile
+        fg_wait(raw_a[1], raw_b[1]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    fg_value(raw_a[1][i]), fg_value(raw_b[1][j]), acc[i][j], 0, 0, 0);
+    }
     // the loads of the tiles past the end still target LDS: let them land before
     // the workgroup can retire and its LDS be handed to another one
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // ---- epilogue.  Accumulator register g of lane l is row 8*(g/4)+4*(l/32)+g%4,
-    // column l%32 of its 32 x 32 tile.  Stores go through a buffer descriptor that
-    // covers the tile's valid rows (rows past M are dropped by the range check);
-    // the part of the address that is the same for the whole wavefront travels in
-    // a scalar register, so no per-element 64-bit address arithmetic is needed. ----
+    // column l%32 of its 32 x 32 tile.  Loads and stores go through buffer
+    // descriptors that cover the tile's valid rows (rows past M are dropped by the
+    // range check); the part of the address that is the same for the whole
+    // wavefront travels in a scalar register, so no per-element 64-bit address
+    // arithmetic is needed. ----
     constexpr int ES = (int)sizeof(OutT);
-    const int ldc = (int)a.ldc;
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int rows_c = min(FG_BM, a.M - m0);
+    const int ldc = (int)a.ldc, ldcin = (int)a.ldcin;
     const __amdgpu_buffer_rsrc_t rsrc_c = fg_make_rsrc(
-        static_cast<OutT*>(a.C) + (int64_t)m0 * a.ldc, (uint32_t)rows_a * (uint32_t)ldc * (uint32_t)ES);
+        static_cast<OutT*>(a.C) + (int64_t)m0 * a.ldc, (uint32_t)rows_c * (uint32_t)ldc * (uint32_t)ES);
+    __amdgpu_buffer_rsrc_t rsrc_in = rsrc_c;
+    if constexpr (HAS_IN)
+        rsrc_in = fg_make_rsrc(a.Cin + (int64_t)m0 * a.ldcin, (uint32_t)rows_c * (uint32_t)ldcin * 4u);
     const int uwm = __builtin_amdgcn_readfirstlane(wm), uwn = __builtin_amdgcn_readfirstlane(wn);
     const int lane_off = (4 * fhalf * ldc + frow) * ES;
+    const int lane_off_in = (4 * fhalf * ldcin + frow) * 4;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int col0 = n0 + uwn * 128 + j * 32;
@@ -243,14 +387,13 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_nt_256(FGArgs a) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int row0 = uwm * 128 + i * 32;
-                if constexpr (ACCUM) {
-                    static_assert(!ACCUM || ES == 4, "accumulation is into fp32");
+                if constexpr (HAS_IN) {
                     float old[16];
 #pragma unroll
                     for (int g = 0; g < 16; ++g) {
-                        const int soff = ((row0 + 8 * (g >> 2) + (g & 3)) * ldc + col0) * ES;
+                        const int soff = ((row0 + 8 * (g >> 2) + (g & 3)) * ldcin + col0) * 4;
                         old[g] = __uint_as_float(
-                            __builtin_amdgcn_raw_buffer_load_b32(rsrc_c, lane_off, soff, 0));
+                            __builtin_amdgcn_raw_buffer_load_b32(rsrc_in, lane_off_in, soff, 0));
                     }
 #pragma unroll
                     for (int g = 0; g < 16; ++g) acc[i][j][g] += old[g];
@@ -258,6 +401,8 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_nt_256(FGArgs a) {
 #pragma unroll
                 for (int g = 0; g < 16; ++g) {
                     const int soff = ((row0 + 8 * (g >> 2) + (g & 3)) * ldc + col0) * ES;
+                    // read the element into a scalar first: a bit_cast applied directly
+                    // to an accumulator vector element is miscompiled by this toolchain
                     const float v = acc[i][j][g];
                     if constexpr (ES == 4) {
                         __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rsrc_c, lane_off, soff,

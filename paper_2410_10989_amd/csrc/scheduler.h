@@ -22,11 +22,18 @@ struct Plan {
     int64_t nchunks = 0;
     int64_t ldz = 0;       // row stride of the logits chunk, elements
     int64_t ldc = 0;       // row stride of the row-transposed scratch, elements
-    bool fp32_dw_acc = false;   // dW is accumulated in an fp32 scratch and cast at the end
+    bool fp32_dw_acc = false;   // dW is accumulated in an fp32 scratch across chunks
+    // which products can run on the tuned bf16 kernel straight from X, W and the
+    // logits chunk; the others need transposed copies and the guarded kernel
+    bool fast_logits = false, fast_dx = false, fast_dw_full = false, fast_dw_last = false;
     // byte offsets into the workspace
     size_t off_hdr = 0, off_row_loss = 0, off_z = 0, off_gt = 0, off_wt = 0, off_xt = 0,
            off_dwacc = 0, total = 0;
 };
+
+// Limits of the tuned kernel's 32-bit tile offsets (see gemm_bf16_nt.h).
+inline bool fits_row_form(int64_t ld, int64_t K) { return (256 * ld + K + 256) * 2 < ((int64_t)1 << 31); }
+inline bool fits_col_form(int64_t ld, int64_t K) { return (K + 192) * ld * 2 < ((int64_t)1 << 31); }
 
 inline Plan make_plan(int64_t BT, int64_t H, int64_t V, int dtype, size_t budget_bytes,
                       bool worst_case_bt = false) {
@@ -36,19 +43,38 @@ inline Plan make_plan(int64_t BT, int64_t H, int64_t V, int dtype, size_t budget
     int64_t cmax = (int64_t)(budget_bytes / ((size_t)p.ldz * es));
     cmax = cmax / CHUNK_ALIGN * CHUNK_ALIGN;
     if (cmax < CHUNK_ALIGN) cmax = CHUNK_ALIGN;
+    int64_t rows_last;
     if (worst_case_bt) {
         p.C = cmax;
         p.nchunks = 2;
+        rows_last = 1;   // a ragged last chunk is the most expensive case
     } else if (BT <= cmax) {
         p.C = BT;
         p.nchunks = 1;
+        rows_last = BT;
     } else {
         p.nchunks = (BT + cmax - 1) / cmax;
         p.C = round_up((BT + p.nchunks - 1) / p.nchunks, CHUNK_ALIGN);   // even out the chunks
         p.nchunks = (BT + p.C - 1) / p.C;
+        rows_last = BT - (p.nchunks - 1) * p.C;
     }
     p.ldc = round_up(p.C, 64);
     p.fp32_dw_acc = (dtype != 0) && p.nchunks > 1;
+
+    if (dtype != 0) {
+        const bool out_ok = 256 * H * 4 < ((int64_t)1 << 31);
+        p.fast_logits = (H % 64 == 0) && fits_row_form(H, H) && 256 * p.ldz * 2 < ((int64_t)1 << 31);
+        p.fast_dx = (V % 64 == 0) && (H % 8 == 0) && fits_row_form(p.ldz, V) && fits_col_form(H, V) &&
+                    out_ok;
+        auto dw_ok = [&](int64_t rows) {
+            return (rows % 64 == 0) && (H % 8 == 0) && fits_col_form(p.ldz, rows) &&
+                   fits_col_form(H, rows) && out_ok;
+        };
+        p.fast_dw_full = (p.nchunks > 1) ? dw_ok(p.C) : dw_ok(rows_last);
+        p.fast_dw_last = dw_ok(rows_last);
+    }
+    const bool need_wt = !p.fast_dx;
+    const bool need_gt = !(p.fast_dw_full && p.fast_dw_last);
 
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -59,9 +85,9 @@ inline Plan make_plan(int64_t BT, int64_t H, int64_t V, int dtype, size_t budget
     p.off_hdr = take(256);
     p.off_row_loss = take((size_t)p.C * sizeof(float));
     p.off_z = take((size_t)p.C * p.ldz * es);
-    p.off_gt = take((size_t)V * p.ldc * es);
-    p.off_wt = take((size_t)H * p.ldz * es);
-    p.off_xt = take((size_t)H * p.ldc * es);
+    p.off_gt = take(need_gt ? (size_t)V * p.ldc * es : 0);
+    p.off_wt = take(need_wt ? (size_t)H * p.ldz * es : 0);
+    p.off_xt = take(need_gt ? (size_t)H * p.ldc * es : 0);
     p.off_dwacc = take(p.fp32_dw_acc ? (size_t)V * H * sizeof(float) : 0);
     p.total = off;
     return p;
