@@ -130,13 +130,13 @@ int launch_gemm_generic(int kind, const T* A, int64_t lda, const T* B, int64_t l
 template <typename OutT, bool HAS_IN, bool A_KM, bool B_KM>
 int launch_gemm_fast(int kind, const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, OutT* C,
                      int64_t ldc, const float* Cin, int64_t ldcin, int64_t M, int64_t N, int64_t K,
-                     hipStream_t s) {
+                     hipStream_t s, int ksplit = 1, int64_t split_stride = 0) {
     if (M <= 0 || N <= 0 || K <= 0) return FLCE_OK;
     if (K % FG_BK != 0 || !aligned(A, 16) || !aligned(B, 16)) return FLCE_ERR_ARG;
     ScopedKernelTimer timer(kind, s);
     FGArgs a{A, lda, B, ldb, C, ldc, Cin, ldcin, (int)M, (int)N, (int)K,
-             (int)((M + FG_BM - 1) / FG_BM), (int)((N + FG_BN - 1) / FG_BN)};
-    const int64_t total = (int64_t)a.tiles_m * a.tiles_n;
+             (int)((M + FG_BM - 1) / FG_BM), (int)((N + FG_BN - 1) / FG_BN), ksplit, split_stride};
+    const int64_t total = (int64_t)a.tiles_m * a.tiles_n * ksplit;
     const dim3 grid((unsigned)((total + FG_XCDS - 1) / FG_XCDS * FG_XCDS));
     hipLaunchKernelGGL((gemm_bf16_256<OutT, HAS_IN, A_KM, B_KM>), grid, dim3(FG_THREADS), 0, s, a);
     HIP_TRY(hipGetLastError());
@@ -221,9 +221,23 @@ int run_fwd_bwd(const T* X, const T* W, const int64_t* targets, int64_t BT, int6
         // dX_c = G W
         if (want_dx) {
             if (BF16 && p.fast_dx) {
-                if constexpr (BF16)
-                    FLCE_TRY((launch_gemm_fast<bf16_t, false, false, true>(
-                        FLCE_KIND_DX_GEMM, Z, p.ldz, W, H, dX + r0 * H, H, nullptr, 0, rows, H, V, s)));
+                if constexpr (BF16) {
+                    if (p.dx_ksplit > 1) {
+                        // few output tiles, very long K: K ranges -> fp32 partials -> fixed-order sum
+                        float* part = reinterpret_cast<float*>(ws + p.off_dxpart);
+                        FLCE_TRY((launch_gemm_fast<float, false, false, true>(
+                            FLCE_KIND_DX_GEMM, Z, p.ldz, W, H, part, H, nullptr, 0, rows, H, V, s,
+                            p.dx_ksplit, p.C * H)));
+                        ScopedKernelTimer timer(FLCE_KIND_DX_GEMM, s);
+                        hipLaunchKernelGGL((splitk_reduce_kernel<bf16_t>), dim3(1024), dim3(256), 0, s,
+                                           part, p.C * H, p.dx_ksplit, dX + r0 * H, rows * H);
+                        HIP_TRY(hipGetLastError());
+                    } else {
+                        FLCE_TRY((launch_gemm_fast<bf16_t, false, false, true>(
+                            FLCE_KIND_DX_GEMM, Z, p.ldz, W, H, dX + r0 * H, H, nullptr, 0, rows, H, V,
+                            s)));
+                    }
+                }
             } else {
                 FLCE_TRY((launch_gemm_generic<T, T>(FLCE_KIND_DX_GEMM, Z, p.ldz, WT, p.ldz, dX + r0 * H,
                                                     H, rows, H, V, false, s)));

@@ -42,6 +42,10 @@
 //    selects the XCD and each XCD walks its own contiguous span of a grouped
 //    (8 tile rows at a time) tile order; tiles that run together on one XCD
 //    share A and B panels in that XCD's L2.
+// With ksplit > 1 the K range is cut into ksplit pieces computed by different
+// workgroups; piece s writes its partial result to C + s * split_stride (fp32), and a
+// separate fixed-order reduction adds the pieces (used when M x N has fewer tiles
+// than the chip has CUs, as for dX with its very long K = V).
 // Requirements (checked on the host): K % 64 == 0, leading dimensions % 8 == 0,
 // A and B 16-byte aligned, every byte offset inside an operand tile below 2^31
 // (row form: (256 * ld + K + 256) * 2; column form: (K + 192) * ld * 2),
@@ -73,6 +77,8 @@ struct FGArgs {
     int64_t ldcin;
     int M, N, K;
     int tiles_m, tiles_n;
+    int ksplit;            // K is cut into this many ranges (>= 1), one workgroup per tile and range
+    int64_t split_stride;  // elements between the partial results of consecutive K ranges in C
 };
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -140,6 +146,12 @@ struct FgOperand {
                 rd[i] = (8 * (g >> 1) + (s >> 2)) * 512 + (((sub * 4 + i) ^ f) * 64) + 32 * (g & 1) +
                         8 * (s & 3);
         }
+    }
+
+    // make K step 0 of the loads below mean K step k_begin of the matrix
+    __device__ __forceinline__ void rebase(int k_begin) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) off[r] += k_begin * kstep;
     }
 
     // start the 8 loads of this wavefront for K step kt into ring slot `slot`
@@ -218,11 +230,13 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
 
-    // ---- workgroup id -> tile (XCD aware, grouped order) ----
-    const int total = a.tiles_m * a.tiles_n;
+    // ---- workgroup id -> (K range, tile) (XCD aware, grouped order) ----
+    const int tiles = a.tiles_m * a.tiles_n;
     const int per_xcd = (int)gridDim.x / FG_XCDS;
-    const int seq = ((int)blockIdx.x % FG_XCDS) * per_xcd + (int)blockIdx.x / FG_XCDS;
-    if (seq >= total) return;
+    const int seq_all = ((int)blockIdx.x % FG_XCDS) * per_xcd + (int)blockIdx.x / FG_XCDS;
+    if (seq_all >= tiles * a.ksplit) return;
+    const int split = seq_all / tiles;
+    const int seq = seq_all - split * tiles;
     const int group_size = FG_GROUP_M * a.tiles_n;
     const int grp = seq / group_size;
     const int first_m = grp * FG_GROUP_M;
@@ -327,7 +341,12 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
         pipeline_barrier();
     };
 
-    const int nk = a.K / FG_BK;
+    // K steps [k_begin, k_begin + nk) belong to this workgroup
+    const int steps_all = a.K / FG_BK;
+    const int k_begin = (int)((int64_t)steps_all * split / a.ksplit);
+    const int nk = (int)((int64_t)steps_all * (split + 1) / a.ksplit) - k_begin;
+    opa.rebase(k_begin);
+    opb.rebase(k_begin);
     opa.load(smem, 0, 0, uwave);
     opb.load(smem, 1, 0, uwave);
     opa.load(smem, 2, 1, uwave);
@@ -372,8 +391,9 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
     const int frow = lane & 31, fhalf = lane >> 5;
     const int rows_c = min(FG_BM, a.M - m0);
     const int ldc = (int)a.ldc, ldcin = (int)a.ldcin;
-    const __amdgpu_buffer_rsrc_t rsrc_c = fg_make_rsrc(
-        static_cast<OutT*>(a.C) + (int64_t)m0 * a.ldc, (uint32_t)rows_c * (uint32_t)ldc * (uint32_t)ES);
+    const __amdgpu_buffer_rsrc_t rsrc_c =
+        fg_make_rsrc(static_cast<OutT*>(a.C) + (int64_t)split * a.split_stride + (int64_t)m0 * a.ldc,
+                     (uint32_t)rows_c * (uint32_t)ldc * (uint32_t)ES);
     __amdgpu_buffer_rsrc_t rsrc_in = rsrc_c;
     if constexpr (HAS_IN)
         rsrc_in = fg_make_rsrc(a.Cin + (int64_t)m0 * a.ldcin, (uint32_t)rows_c * (uint32_t)ldcin * 4u);

@@ -10,6 +10,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <algorithm>
+
 namespace flce {
 
 constexpr int64_t CHUNK_ALIGN = 256;   // chunk rows are a multiple of the GEMM macro tile
@@ -26,10 +28,30 @@ struct Plan {
     // which products can run on the tuned bf16 kernel straight from X, W and the
     // logits chunk; the others need transposed copies and the guarded kernel
     bool fast_logits = false, fast_dx = false, fast_dw_full = false, fast_dw_last = false;
+    int dx_ksplit = 1;     // K ranges of the dX product (K = V), > 1 when C x H has few tiles
     // byte offsets into the workspace
     size_t off_hdr = 0, off_row_loss = 0, off_z = 0, off_gt = 0, off_wt = 0, off_xt = 0,
-           off_dwacc = 0, total = 0;
+           off_dwacc = 0, off_dxpart = 0, total = 0;
 };
+
+// How many K ranges to cut a product with `tiles` output tiles and `ksteps` K steps
+// into, so that tiles * ranges fills whole rounds of the chip's 256 CUs.  Prefers
+// few ranges (each costs an fp32 partial result) and keeps ranges long.
+inline int choose_ksplit(int64_t tiles, int64_t ksteps) {
+    constexpr int64_t CUS = 256, MIN_STEPS = 64;
+    if (tiles >= CUS) return 1;
+    int best = 1;
+    double best_eff = 0.0;
+    for (int s = 1; s <= 16 && ksteps / s >= MIN_STEPS; ++s) {
+        const int64_t work = tiles * s;
+        const double eff = (double)work / (double)(((work + CUS - 1) / CUS) * CUS);
+        if (eff > best_eff + 0.02) {
+            best_eff = eff;
+            best = s;
+        }
+    }
+    return best;
+}
 
 // Limits of the tuned kernel's 32-bit tile offsets (see gemm_bf16_nt.h).
 inline bool fits_row_form(int64_t ld, int64_t K) { return (256 * ld + K + 256) * 2 < ((int64_t)1 << 31); }
@@ -73,6 +95,10 @@ inline Plan make_plan(int64_t BT, int64_t H, int64_t V, int dtype, size_t budget
         p.fast_dw_full = (p.nchunks > 1) ? dw_ok(p.C) : dw_ok(rows_last);
         p.fast_dw_last = dw_ok(rows_last);
     }
+    if (p.fast_dx) {
+        const int64_t rows = p.nchunks > 1 ? p.C : rows_last;
+        p.dx_ksplit = choose_ksplit(((rows + 255) / 256) * ((H + 255) / 256), V / 64);
+    }
     const bool need_wt = !p.fast_dx;
     const bool need_gt = !(p.fast_dw_full && p.fast_dw_last);
 
@@ -89,6 +115,15 @@ inline Plan make_plan(int64_t BT, int64_t H, int64_t V, int dtype, size_t budget
     p.off_wt = take(need_wt ? (size_t)H * p.ldz * es : 0);
     p.off_xt = take(need_gt ? (size_t)H * p.ldc * es : 0);
     p.off_dwacc = take(p.fp32_dw_acc ? (size_t)V * H * sizeof(float) : 0);
+    size_t dxpart = p.dx_ksplit > 1 ? (size_t)p.dx_ksplit * p.C * H * sizeof(float) : 0;
+    if (worst_case_bt && p.fast_dx) {
+        // the bound has to hold for every chunk size the scheduler can pick
+        for (int64_t c = CHUNK_ALIGN; c <= cmax; c += CHUNK_ALIGN) {
+            const int ks = choose_ksplit((c / 256) * ((H + 255) / 256), V / 64);
+            if (ks > 1) dxpart = std::max(dxpart, (size_t)ks * c * H * sizeof(float));
+        }
+    }
+    p.off_dxpart = take(dxpart);
     p.total = off;
     return p;
 }
