@@ -276,13 +276,15 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
     // One quarter of a K step: the 16 MFMAs of one K=16 sub-step on the fragments in
     // register buffer MB, interleaved with the 8 fragment reads of sub-step KK of the
     // tile in slots (SA, SB) into buffer 1-MB (one fragment per MFMA, in the order
-    // a0 b0 b1 b2 b3 a1 a2 a3 in which the next quarter consumes them), and with the 8
-    // loads of one operand tile (DMA = 1: B tile of step kt into slot SD, DMA = 2: A
-    // tile) behind the last 8 MFMAs.
-    auto quarter = [&](auto mb_, auto kk_, auto sa_, auto sb_, auto dma_, auto sd_, int kt) {
+    // a0 b0 b1 b2 b3 a1 a2 a3 in which the next quarter consumes them), and with 4 of
+    // the 16 loads of the step, one behind every fourth MFMA (DMA = 1: loads R0..R0+3
+    // of the B tile of step kt into slot SD, DMA = 2: of the A tile).  Loads issued in
+    // bursts fill the memory pipe's queue and stall the wavefront, and with it the
+    // matrix pipe: measured 500 extra cycles for 8 back-to-back loads.
+    auto quarter = [&](auto mb_, auto kk_, auto sa_, auto sb_, auto dma_, auto sd_, auto r0_, int kt) {
         constexpr int MB = decltype(mb_)::value, RB = 1 - MB, KK = decltype(kk_)::value;
         constexpr int SA = decltype(sa_)::value, SB = decltype(sb_)::value;
-        constexpr int DMA = decltype(dma_)::value, SD = decltype(sd_)::value;
+        constexpr int DMA = decltype(dma_)::value, SD = decltype(sd_)::value, R0 = decltype(r0_)::value;
         fg_wait(raw_a[MB], raw_b[MB]);
         bf16x8 fa[4], fb[4];
 #pragma unroll
@@ -294,28 +296,29 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
         __builtin_amdgcn_sched_barrier(0);
 #define FG_MFMA(q) \
         acc[(q) >> 2][(q) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[(q) >> 2], fb[(q) & 3], acc[(q) >> 2][(q) & 3], 0, 0, 0)
-#define FG_DMA(q)                                                              \
-        if constexpr (DMA == 1) opb.load_one(smem, SD, kt, uwave, (q) - 8);    \
-        if constexpr (DMA == 2) opa.load_one(smem, SD, kt, uwave, (q) - 8);    \
-        __builtin_amdgcn_sched_barrier(0)
-        FG_MFMA(0);  fg_issue<KK, 0>(raw_a[RB][0], opa, sa_addr); __builtin_amdgcn_sched_barrier(0);
-        FG_MFMA(1);  fg_issue<KK, 0>(raw_b[RB][0], opb, sb_addr); __builtin_amdgcn_sched_barrier(0);
-        FG_MFMA(2);  fg_issue<KK, 1>(raw_b[RB][1], opb, sb_addr); __builtin_amdgcn_sched_barrier(0);
-        FG_MFMA(3);  fg_issue<KK, 2>(raw_b[RB][2], opb, sb_addr); __builtin_amdgcn_sched_barrier(0);
-        FG_MFMA(4);  fg_issue<KK, 3>(raw_b[RB][3], opb, sb_addr); __builtin_amdgcn_sched_barrier(0);
-        FG_MFMA(5);  fg_issue<KK, 1>(raw_a[RB][1], opa, sa_addr); __builtin_amdgcn_sched_barrier(0);
-        FG_MFMA(6);  fg_issue<KK, 2>(raw_a[RB][2], opa, sa_addr); __builtin_amdgcn_sched_barrier(0);
-        FG_MFMA(7);  fg_issue<KK, 3>(raw_a[RB][3], opa, sa_addr); __builtin_amdgcn_sched_barrier(0);
-        FG_MFMA(8);  FG_DMA(8);
-        FG_MFMA(9);  FG_DMA(9);
-        FG_MFMA(10); FG_DMA(10);
-        FG_MFMA(11); FG_DMA(11);
-        FG_MFMA(12); FG_DMA(12);
-        FG_MFMA(13); FG_DMA(13);
-        FG_MFMA(14); FG_DMA(14);
-        FG_MFMA(15); FG_DMA(15);
+#define FG_DMA(n)                                                          \
+        if constexpr (DMA == 1) opb.load_one(smem, SD, kt, uwave, R0 + (n));   \
+        if constexpr (DMA == 2) opa.load_one(smem, SD, kt, uwave, R0 + (n))
+#define FG_END __builtin_amdgcn_sched_barrier(0)
+        FG_MFMA(0);  fg_issue<KK, 0>(raw_a[RB][0], opa, sa_addr); FG_END;
+        FG_MFMA(1);  fg_issue<KK, 0>(raw_b[RB][0], opb, sb_addr); FG_END;
+        FG_MFMA(2);  fg_issue<KK, 1>(raw_b[RB][1], opb, sb_addr); FG_DMA(0); FG_END;
+        FG_MFMA(3);  fg_issue<KK, 2>(raw_b[RB][2], opb, sb_addr); FG_END;
+        FG_MFMA(4);  fg_issue<KK, 3>(raw_b[RB][3], opb, sb_addr); FG_END;
+        FG_MFMA(5);  fg_issue<KK, 1>(raw_a[RB][1], opa, sa_addr); FG_END;
+        FG_MFMA(6);  fg_issue<KK, 2>(raw_a[RB][2], opa, sa_addr); FG_DMA(1); FG_END;
+        FG_MFMA(7);  fg_issue<KK, 3>(raw_a[RB][3], opa, sa_addr); FG_END;
+        FG_MFMA(8);  FG_END;
+        FG_MFMA(9);  FG_END;
+        FG_MFMA(10); FG_DMA(2); FG_END;
+        FG_MFMA(11); FG_END;
+        FG_MFMA(12); FG_END;
+        FG_MFMA(13); FG_END;
+        FG_MFMA(14); FG_DMA(3); FG_END;
+        FG_MFMA(15); FG_END;
 #undef FG_MFMA
 #undef FG_DMA
+#undef FG_END
     };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
@@ -334,10 +337,11 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
         using SB = std::integral_constant<int, (2 * PH + 1) % 5>;
         using SB1 = std::integral_constant<int, (2 * PH + 3) % 5>;
         using SA2 = std::integral_constant<int, (2 * PH + 4) % 5>;
-        quarter(I1{}, I0{}, SA{}, SB{}, I1{}, SB1{}, t + 1);   // MFMA: sub-step 3 of tile t-1
-        quarter(I0{}, I1{}, SA{}, SB{}, I2{}, SA2{}, t + 2);   // MFMA: sub-step 0
-        quarter(I1{}, I2{}, SA{}, SB{}, I0{}, I0{}, 0);        // MFMA: sub-step 1
-        quarter(I0{}, I3{}, SA{}, SB{}, I0{}, I0{}, 0);        // MFMA: sub-step 2
+        using I4 = std::integral_constant<int, 4>;
+        quarter(I1{}, I0{}, SA{}, SB{}, I1{}, SB1{}, I0{}, t + 1);   // MFMA: sub-step 3 of tile t-1
+        quarter(I0{}, I1{}, SA{}, SB{}, I1{}, SB1{}, I4{}, t + 1);   // MFMA: sub-step 0
+        quarter(I1{}, I2{}, SA{}, SB{}, I2{}, SA2{}, I0{}, t + 2);   // MFMA: sub-step 1
+        quarter(I0{}, I3{}, SA{}, SB{}, I2{}, SA2{}, I4{}, t + 2);   // MFMA: sub-step 2
         pipeline_barrier();
     };
 
