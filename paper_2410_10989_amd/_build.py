@@ -44,6 +44,12 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+    # A shared library links even when a kernel's host-side launch stub was not
+    # emitted; it would only fail when loaded.  Catch that here.
+    nm = subprocess.run(["nm", "-D", "--undefined-only", LIB_PATH], stdout=subprocess.PIPE, text=True)
+    missing = [l.split()[-1] for l in nm.stdout.splitlines() if "__device_stub__" in l]
+    if missing:
+        raise RuntimeError("libflce.so has undefined kernel launch stubs: " + ", ".join(missing))
     return LIB_PATH
 
 
