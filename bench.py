@@ -22,10 +22,12 @@ if ROOT not in sys.path:
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense matrix peaks
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs, scaled by a copy kernel of known size; see profiles/.  None
-# until such a run has been recorded for the current kernel.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = None
+# HBM bytes per launch of the dominant kernel (logits product at config 3) from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, each scaled by what
+# the same counter reads for the 1 GiB copy of --calibrate-copy; the summary of
+# those runs is profiles/gemm_bf16_256_config3_hbm_traffic.txt.  Only valid for
+# the default workload.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 8.83e9
 
 
 def main():
@@ -37,6 +39,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=1024)
     ap.add_argument("--budget-mib", type=int, default=0, help="logits chunk budget override")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run one plain 1 GiB device copy first (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path is a single-GPU kernel "
@@ -70,6 +74,13 @@ def main():
     print(f"# inputs {w.name} BT={w.BT} H={w.H} V={w.V} {w.dtype} generated+uploaded in "
           f"{time.time() - t0:.1f} s", file=sys.stderr, flush=True)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)            # 1 GiB read + 1 GiB written by one copy kernel
+        torch.cuda.synchronize()
+        del src, dst
+
     def step():
         flce.flce_fwd_bwd(X, W, t, w.ignore_index, loss=loss, dX=dX, dW=dW)
 
@@ -93,10 +104,13 @@ def main():
     tflops = flops_step / (ms_per_step * 1e-3) / 1e12
     peak = MFMA_PEAK_TFLOPS[w.dtype]
 
-    # dominant kernel class = the one with the largest total time
-    gemm_kinds = ("logits_gemm", "dx_gemm", "dw_gemm")
-    dom = max(gemm_kinds, key=lambda k: kt[k][0])
+    # Dominant kernel = the kernel symbol with the largest total time.  The logits and
+    # dX products are one symbol each; with several chunks the dW product runs as
+    # two symbols (fp32 partial sums, then the bf16 result), so its time is split.
     nchunks = flce.flce_num_chunks(w.BT, w.H, w.V, code)
+    gemm_kinds = ("logits_gemm", "dx_gemm", "dw_gemm")
+    symbols = {"logits_gemm": 1, "dx_gemm": 1, "dw_gemm": 2 if nchunks > 1 else 1}
+    dom = max(gemm_kinds, key=lambda k: kt[k][0] / symbols[k])
     dom_ms, dom_n = kt[dom]
     flops_per_launch = 2.0 * w.BT * w.H * w.V * args.steps / max(dom_n, 1)   # mean over its launches
     dom_avg_ms = dom_ms / max(dom_n, 1)
@@ -132,7 +146,7 @@ def main():
                      "unit": "TFLOP/s", "frac": achieved / peak,
                      "avg_launch_ms": dom_avg_ms, "launches": dom_n,
                      "flops_per_launch": flops_per_launch,
-                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH},
+                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH if args.config == 3 else None},
     }
 
     if not args.no_cpu_baseline:
