@@ -47,9 +47,9 @@
 // separate fixed-order reduction adds the pieces (used when M x N has fewer tiles
 // than the chip has CUs, as for dX with its very long K = V).
 // Requirements (checked on the host): K % 64 == 0, leading dimensions % 8 == 0,
-// A and B 16-byte aligned, every byte offset inside an operand tile below 2^31
-// (row form: (256 * ld + K + 256) * 2; column form: (K + 192) * ld * 2),
-// 256 * ldc * sizeof(element) < 2^31 for C and Cin.  M and N are arbitrary:
+// A and B 16-byte aligned, the byte extent of one tile below 2^30 (row form:
+// 256 * ld * 2 + 128, column form: 64 * ld * 2 + 512; operands themselves may be of
+// any size), 256 * ldc * sizeof(element) < 2^31 for C and Cin.  M and N are arbitrary:
 // tile rows / columns past them hold zeros or stale values and only feed outputs
 // that are never stored.
 #pragma once
@@ -95,7 +95,14 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t fg_make_rsrc(const void* base,
 // 8*(l/32) .. +7) are read back.  KM = false: row form, KM = true: column form.
 template <bool KM>
 struct FgOperand {
+    // The buffer descriptor covers the operand from K step kt_base on; the loads of K
+    // step kt add (kt - kt_base) * kstep as scalar offset.  All offsets are 32-bit, so
+    // the descriptor is moved forward every seg_steps K steps (a rarely taken uniform
+    // branch; for most operands never), which lets operands be of any size.
+    const unsigned char* base0;   // first byte of K step kt_base of this workgroup's tiles
+    int64_t bytes;                // bytes from base0 to the end of the operand's valid range
     __amdgpu_buffer_rsrc_t rsrc;
+    int kt_base, seg_steps;
     int off[8];   // per-lane byte offset of each of the 8 loads a wavefront issues per tile
     int kstep;    // bytes between consecutive K steps
     int rd[4];    // per-lane LDS byte offsets of the fragment reads
@@ -112,7 +119,8 @@ struct FgOperand {
             // physical position (row l/8, piece l%8) and fetches the logical piece
             // (l%8) ^ swizzle(row); wavefront w fills rows 8w..8w+7 of every 32-row group
             const int rows = min(FG_BM, extent - r0);
-            rsrc = fg_make_rsrc(base + (int64_t)r0 * ld, (uint32_t)rows * (uint32_t)ildb);
+            base0 = reinterpret_cast<const unsigned char*>(base + (int64_t)r0 * ld);
+            bytes = (int64_t)rows * ildb;
             const int ld_row = tid >> 3;
             const int piece = (tid & 7) ^ ((ld_row >> 1) & 7);
 #pragma unroll
@@ -127,7 +135,8 @@ struct FgOperand {
             // w covers K rows 8r + 2w and 8r + 2w + 1; lane l owns the physical 16-byte
             // piece l%32 of row l/32 and fetches the logical 64-byte chunk
             // (piece / 4) ^ f(k), f(k) = k%4 + 4 * ((k/8) % 2)
-            rsrc = fg_make_rsrc(base + r0, ((uint32_t)K * (uint32_t)ld - (uint32_t)r0) * 2u);
+            base0 = reinterpret_cast<const unsigned char*>(base + r0);
+            bytes = ((int64_t)K * ld - r0) * 2;
 #pragma unroll
             for (int r = 0; r < 8; ++r) {
                 const int k = 8 * r + 2 * wave + (lane >> 5);
@@ -148,15 +157,32 @@ struct FgOperand {
         }
     }
 
-    // make K step 0 of the loads below mean K step k_begin of the matrix
-    __device__ __forceinline__ void rebase(int k_begin) {
-#pragma unroll
-        for (int r = 0; r < 8; ++r) off[r] += k_begin * kstep;
+    __device__ __forceinline__ void make_rsrc() {
+        const int64_t left = bytes < 0 ? 0 : (bytes > 0xFFFFFFFFll ? 0xFFFFFFFFll : bytes);
+        rsrc = fg_make_rsrc(base0, (uint32_t)left);
+    }
+    // K step 0 of the loads below is K step k_begin of the matrix
+    __device__ __forceinline__ void start_at(int k_begin) {
+        base0 += (int64_t)k_begin * kstep;
+        bytes -= (int64_t)k_begin * kstep;
+        kt_base = 0;
+        seg_steps = max(1, (1 << 30) / kstep);
+        make_rsrc();
+    }
+    // call before the first load of K step kt (kt never decreases)
+    __device__ __forceinline__ void before_step(int kt) {
+        if (kt - kt_base >= seg_steps) {
+            base0 += (int64_t)seg_steps * kstep;
+            bytes -= (int64_t)seg_steps * kstep;
+            kt_base += seg_steps;
+            make_rsrc();
+        }
     }
 
     // start the 8 loads of this wavefront for K step kt into ring slot `slot`
-    __device__ __forceinline__ void load(unsigned char* smem, int slot, int kt, int uwave) const {
-        const int soff = kt * kstep;
+    __device__ __forceinline__ void load(unsigned char* smem, int slot, int kt, int uwave) {
+        before_step(kt);
+        const int soff = (kt - kt_base) * kstep;
         unsigned char* dst = smem + slot * FG_TILE_BYTES + uwave * 1024;
 #pragma unroll
         for (int r = 0; r < 8; ++r)
@@ -167,7 +193,8 @@ struct FgOperand {
     // start one of the 8 loads of this wavefront for K step kt into ring slot `slot`
     __device__ __forceinline__ void load_one(unsigned char* smem, int slot, int kt, int uwave, int r) const {
         unsigned char* dst = smem + slot * FG_TILE_BYTES + uwave * 1024 + r * 4096;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (fg_lds_ptr)dst, 16, off[r], kt * kstep, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (fg_lds_ptr)dst, 16, off[r], (kt - kt_base) * kstep,
+                                                 0, 0);
     }
 };
 
@@ -285,6 +312,8 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
         constexpr int MB = decltype(mb_)::value, RB = 1 - MB, KK = decltype(kk_)::value;
         constexpr int SA = decltype(sa_)::value, SB = decltype(sb_)::value;
         constexpr int DMA = decltype(dma_)::value, SD = decltype(sd_)::value, R0 = decltype(r0_)::value;
+        if constexpr (DMA == 1 && R0 == 0) opb.before_step(kt);
+        if constexpr (DMA == 2 && R0 == 0) opa.before_step(kt);
         fg_wait(raw_a[MB], raw_b[MB]);
         bf16x8 fa[4], fb[4];
 #pragma unroll
@@ -349,8 +378,8 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
     const int steps_all = a.K / FG_BK;
     const int k_begin = (int)((int64_t)steps_all * split / a.ksplit);
     const int nk = (int)((int64_t)steps_all * (split + 1) / a.ksplit) - k_begin;
-    opa.rebase(k_begin);
-    opb.rebase(k_begin);
+    opa.start_at(k_begin);
+    opb.start_at(k_begin);
     opa.load(smem, 0, 0, uwave);
     opb.load(smem, 1, 0, uwave);
     opa.load(smem, 2, 1, uwave);

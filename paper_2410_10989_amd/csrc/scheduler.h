@@ -53,9 +53,9 @@ inline int choose_ksplit(int64_t tiles, int64_t ksteps) {
     return best;
 }
 
-// Limits of the tuned kernel's 32-bit tile offsets (see gemm_bf16_nt.h).
-inline bool fits_row_form(int64_t ld, int64_t K) { return (256 * ld + K + 256) * 2 < ((int64_t)1 << 31); }
-inline bool fits_col_form(int64_t ld, int64_t K) { return (K + 192) * ld * 2 < ((int64_t)1 << 31); }
+// Limits of the tuned kernel's 32-bit offsets inside one tile (see gemm_bf16_nt.h).
+inline bool fits_row_form(int64_t ld, int64_t) { return 256 * ld * 2 + 128 < ((int64_t)1 << 30); }
+inline bool fits_col_form(int64_t ld, int64_t) { return 64 * ld * 2 + 512 < ((int64_t)1 << 30); }
 
 inline Plan make_plan(int64_t BT, int64_t H, int64_t V, int dtype, size_t budget_bytes,
                       bool worst_case_bt = false) {

@@ -19,6 +19,23 @@ GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 @pytest.mark.parametrize("idx", [2, 3, 4, 5])
 def test_full_size_config_against_stored_oracle(idx):
+    _run_full_size(idx)
+
+
+def test_full_size_single_chunk_above_2gib():
+    # One chunk of 8192 rows: the 2.1 GB dlogits buffer is read K-major by the dW
+    # product, whose 32-bit tile offsets then need the descriptor moved mid-way.
+    import paper_2410_10989_amd as flce
+    old = flce.flce_get_logits_budget_bytes()
+    try:
+        flce.flce_set_logits_budget_bytes(2304 << 20)
+        assert flce.flce_num_chunks(8192, 4096, 128256, flce.FLCE_BF16) == 1
+        _run_full_size(3)
+    finally:
+        flce.flce_set_logits_budget_bytes(old)
+
+
+def _run_full_size(idx):
     import paper_2410_10989_amd as flce
     name = workloads.CONFIGS[idx - 1]["name"]
     ref = np.load(os.path.join(GOLDEN, f"config{idx}_{name}.npz"))
