@@ -30,6 +30,57 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 8.83e9
 
 
+def bench_cross_entropy(args):
+    """Stand-alone cross entropy forward+backward (logits given, gradient written in
+    place) at the vocabulary sizes of the paper's kernel benchmark (section 4.1:
+    40960 ... 163840), bf16 logits, 4096 rows.  HBM-bound: the algorithmic traffic
+    is one read and one write of the logits."""
+    import torch
+
+    import paper_2410_10989_amd as flce
+
+    BT = 4096
+    rows = []
+    for V in (40960, 81920, 122880, 163840):
+        g = torch.Generator(device="cuda").manual_seed(241010989 + V)
+        Z0 = (torch.randn(BT, V, generator=g, device="cuda") * 1.3).to(torch.bfloat16)
+        t = torch.randint(0, V, (BT,), generator=g, device="cuda")
+        t[::10] = -100
+        Z = torch.empty_like(Z0)
+        loss = torch.empty((), dtype=torch.float32, device="cuda")
+        times = []
+        for it in range(args.warmup + args.steps):
+            Z.copy_(Z0)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flce.flce_cross_entropy_inplace(Z, t, -100, loss=loss)
+            e1.record()
+            torch.cuda.synchronize()
+            if it >= args.warmup:
+                times.append(e0.elapsed_time(e1))
+        times.sort()
+        med = times[len(times) // 2]
+        algo_bytes = 2.0 * BT * V * 2
+        rows.append({"V": V, "ms_median": med, "ms_q20": times[int(0.2 * (len(times) - 1))],
+                     "ms_q80": times[int(0.8 * (len(times) - 1))],
+                     "algorithmic_gbs": algo_bytes / (med * 1e-3) / 1e9,
+                     "frac_of_hbm_peak": algo_bytes / (med * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "loss": float(loss.item())})
+        del Z0, Z
+    head = rows[-1]
+    print(json.dumps({
+        "metric": "cross entropy fwd+bwd tokens/s (logits given, in-place gradient)",
+        "value": BT / (head["ms_median"] * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_median"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "standalone_ce:BT=4096,V=163840 (headline of the sweep)", "BT": BT},
+        "roofline": {"bound": "hbm", "achieved": head["algorithmic_gbs"], "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": head["frac_of_hbm_peak"], "traffic": None},
+        "sweep": rows}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -39,6 +90,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=1024)
     ap.add_argument("--budget-mib", type=int, default=0, help="logits chunk budget override")
+    ap.add_argument("--mode", choices=("flce", "ce"), default="flce",
+                    help="flce: the fused path (default); ce: stand-alone cross entropy on given "
+                         "logits, swept over the vocabulary sizes of the paper's kernel benchmark")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one plain 1 GiB device copy first (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -55,6 +109,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.mode == "ce":
+        return bench_cross_entropy(args)
     if args.budget_mib:
         flce.flce_set_logits_budget_bytes(args.budget_mib << 20)
 
