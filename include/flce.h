@@ -94,6 +94,39 @@ FLCE_API int flce_fwd_bwd_ex(const void* X, const void* W, const int64_t* target
                     unsigned flags, void* stream);
 
 /*
+ * Several output heads on the same hidden states (paper section 4.2, Medusa
+ * paragraph: extra decoding heads, head j trained to predict the token j + 1
+ * positions further on, each with a cross-entropy loss of its own, all sharing
+ * the backbone's hidden states).  For heads j = 0 .. n_heads-1 with weights W[j]
+ * and targets[j]:
+ *
+ *     loss_j  = mean CE of head j over ITS valid rows (as in flce_fwd_bwd)
+ *     loss    = sum_j weights[j] * loss_j
+ *     dW[j]   = d loss / d W[j]        dX = d loss / d X = sum_j (head j's dX)
+ *
+ * None of the heads' logits is stored whole: the heads run one after the other
+ * through the same chunk loop and the same workspace, so peak extra memory is
+ * that of a single head.  dX is summed in its storage type: head 0 writes it,
+ * every later head adds its fp32 product to the stored value and rounds once.
+ *
+ *   W, targets, dW   HOST arrays of n_heads DEVICE pointers ([V x H] dtype,
+ *                    [BT] int64, [V x H] dtype); read before the call returns.
+ *                    The dW[j] must be distinct buffers.
+ *   weights          HOST array of n_heads finite floats, NULL = all 1
+ *   n_heads          1 .. 16
+ *   loss             device, 1 float          out (weighted sum)
+ *   head_losses      device, n_heads floats   out (unweighted loss_j), may be NULL
+ *   flags            FLCE_SKIP_DX: dX may be NULL;  FLCE_SKIP_DW: dW may be NULL
+ * Shifting the targets per head (and marking the rows that run off the end of a
+ * sequence with ignore_index) is the caller's job.  With n_heads = 1 and
+ * weights = NULL this is flce_fwd_bwd_ex.
+ */
+FLCE_API int flce_multihead_fwd_bwd(const void* X, const void* const* W, const int64_t* const* targets,
+                           const float* weights, int n_heads, int64_t BT, int64_t H, int64_t V,
+                           int64_t ignore_index, int dtype, float* loss, float* head_losses,
+                           void* dX, void* const* dW, unsigned flags, void* stream);
+
+/*
  * Stand-alone cross entropy on given logits (paper section 3.2, CE paragraph):
  * Z[BT x V] (device, dtype, row stride ldz elements, ldz >= V) is replaced in
  * place by dL/dZ; loss receives the mean over valid rows.  Needs no workspace

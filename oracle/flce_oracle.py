@@ -103,6 +103,39 @@ def flce(X, W, targets, ignore_index=-100, rows=None, vocab=None, want_dX=True, 
     return OracleResult(float(loss[0]), lse, dX, dW, G)
 
 
+@dataclass
+class MultiHeadResult:
+    loss: float                # sum_j weights[j] * head_losses[j]
+    head_losses: list          # unweighted mean loss of each head
+    dX: np.ndarray | None      # [BT, H] fp64, gradient of `loss`
+    dWs: list | None           # per head [V, H] fp64, gradient of `loss`
+
+
+def flce_multihead(X, Ws, targets, weights=None, ignore_index=-100, want_dX=True,
+                   want_dW=True) -> MultiHeadResult:
+    """Several heads on the same hidden states (paper section 4.2, Medusa
+    paragraph): every head has a mean cross-entropy loss of its own over its own
+    valid rows, and the training loss is their weighted sum.  Differentiation is
+    linear, so the gradient of the sum is the weighted sum of each head's
+    gradients: dX adds up over the heads, dW_j comes from head j alone."""
+    n = len(Ws)
+    assert len(targets) == n
+    weights = [1.0] * n if weights is None else [float(w) for w in weights]
+    assert len(weights) == n
+    total, head_losses = 0.0, []
+    dX = np.zeros(X.shape, dtype=np.float64) if want_dX else None
+    dWs = [] if want_dW else None
+    for W, t, w in zip(Ws, targets, weights):
+        r = flce(X, W, t, ignore_index, want_dX=want_dX, want_dW=want_dW)
+        head_losses.append(r.loss)
+        total += w * r.loss
+        if want_dX:
+            dX += w * r.dX
+        if want_dW:
+            dWs.append(w * r.dW)
+    return MultiHeadResult(total, head_losses, dX, dWs)
+
+
 def cross_entropy(Z, targets, ignore_index=-100):
     """Stand-alone CE on given logits Z [BT, V] (fp64): (loss, dlogits, lse)."""
     lib = _load()

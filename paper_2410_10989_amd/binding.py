@@ -37,6 +37,7 @@ def lib() -> ctypes.CDLL:
         sigs = {
             "flce_fwd_bwd": ([p, p, p, i64, i64, i64, i64, ci, p, p, p, p], ci),
             "flce_fwd_bwd_ex": ([p, p, p, i64, i64, i64, i64, ci, p, p, p, u, p], ci),
+            "flce_multihead_fwd_bwd": ([p, p, p, p, ci, i64, i64, i64, i64, ci, p, p, p, p, u, p], ci),
             "flce_cross_entropy_inplace": ([p, p, i64, i64, i64, i64, ci, p, p], ci),
             "flce_workspace_bytes": ([i64, i64, i64, ci], sz),
             "flce_workspace_bytes_max": ([i64, i64, ci], sz),
@@ -123,6 +124,56 @@ def flce_fwd_bwd(X, W, targets, ignore_index=-100, loss=None, dX=None, dW=None, 
                                    _stream_handle(stream))
     _check(st, "flce_fwd_bwd")
     return loss, dX, dW
+
+
+def flce_multihead_fwd_bwd(X, Ws, targets, weights=None, ignore_index=-100, loss=None,
+                           head_losses=None, dX=None, dWs=None, flags=0, stream=None):
+    """Several heads on shared hidden states: loss = sum_j weights[j] * CE_j.
+
+    X [BT, H]; Ws, targets: sequences of n_heads tensors W_j [V, H] and int64
+    targets_j [BT]; weights: n_heads floats or None (all 1).  Returns
+    (loss, head_losses [n_heads], dX, [dW_j]).  Outputs are allocated when not passed.
+    """
+    code = _dtype_code(X)
+    n = len(Ws)
+    if n < 1 or len(targets) != n or (weights is not None and len(weights) != n):
+        raise ValueError("Ws, targets and weights must have one entry per head")
+    if X.dim() != 2:
+        raise ValueError("expected X [BT, H]")
+    BT, H = X.shape
+    V = Ws[0].shape[0]
+    for W, t in zip(Ws, targets):
+        if W.dtype != X.dtype or t.dtype != torch.int64:
+            raise TypeError("every W must have X's dtype and every targets tensor must be int64")
+        if W.shape != (V, H) or t.shape != (BT,):
+            raise ValueError("expected every W [V, H] and every targets [BT]")
+    if loss is None:
+        loss = torch.empty((), dtype=torch.float32, device=X.device)
+    if head_losses is None:
+        head_losses = torch.empty(n, dtype=torch.float32, device=X.device)
+    if head_losses.shape != (n,) or head_losses.dtype != torch.float32:
+        raise ValueError("head_losses must be n_heads float32 values")
+    if dX is None and not (flags & SKIP_DX):
+        dX = torch.empty_like(X)
+    if dX is not None and (dX.shape != X.shape or dX.dtype != X.dtype):
+        raise ValueError("dX must match X in shape and dtype")
+    if dWs is None and not (flags & SKIP_DW):
+        dWs = [torch.empty_like(W) for W in Ws]
+    if dWs is not None:
+        if len(dWs) != n or any(d.shape != (V, H) or d.dtype != X.dtype for d in dWs):
+            raise ValueError("dWs must hold one [V, H] tensor of X's dtype per head")
+    ptr_array = ctypes.c_void_p * n
+    w_arr = ptr_array(*[_dev_ptr(W, "W") for W in Ws])
+    t_arr = ptr_array(*[_dev_ptr(t, "targets") for t in targets])
+    dw_arr = ptr_array(*[_dev_ptr(d, "dW") for d in dWs]) if dWs is not None else None
+    wt_arr = (ctypes.c_float * n)(*[float(w) for w in weights]) if weights is not None else None
+    with torch.cuda.device(X.device):
+        st = lib().flce_multihead_fwd_bwd(_dev_ptr(X, "X"), w_arr, t_arr, wt_arr, n, BT, H, V,
+                                          int(ignore_index), code, _dev_ptr(loss, "loss"),
+                                          _dev_ptr(head_losses, "head_losses"), _dev_ptr(dX, "dX"),
+                                          dw_arr, int(flags), _stream_handle(stream))
+    _check(st, "flce_multihead_fwd_bwd")
+    return loss, head_losses, dX, dWs
 
 
 def flce_cross_entropy_inplace(Z, targets, ignore_index=-100, loss=None, stream=None):

@@ -125,11 +125,11 @@ int launch_gemm_generic(int kind, const T* A, int64_t lda, const T* B, int64_t l
     return FLCE_OK;
 }
 
-// Tuned bf16 kernel (see gemm_bf16_nt.h for what A_KM / B_KM / HAS_IN mean).  The
+// Tuned bf16 kernel (see gemm_bf16_nt.h for what A_KM / B_KM / InT mean).  The
 // caller has checked the shape limits (Plan::fast_*).
-template <typename OutT, bool HAS_IN, bool A_KM, bool B_KM>
+template <typename OutT, typename InT, bool A_KM, bool B_KM>
 int launch_gemm_fast(int kind, const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, OutT* C,
-                     int64_t ldc, const float* Cin, int64_t ldcin, int64_t M, int64_t N, int64_t K,
+                     int64_t ldc, const InT* Cin, int64_t ldcin, int64_t M, int64_t N, int64_t K,
                      hipStream_t s, int ksplit = 1, int64_t split_stride = 0) {
     if (M <= 0 || N <= 0 || K <= 0) return FLCE_OK;
     if (K % FG_BK != 0 || !aligned(A, 16) || !aligned(B, 16)) return FLCE_ERR_ARG;
@@ -138,7 +138,7 @@ int launch_gemm_fast(int kind, const bf16_t* A, int64_t lda, const bf16_t* B, in
              (int)((M + FG_BM - 1) / FG_BM), (int)((N + FG_BN - 1) / FG_BN), ksplit, split_stride};
     const int64_t total = (int64_t)a.tiles_m * a.tiles_n * ksplit;
     const dim3 grid((unsigned)((total + FG_XCDS - 1) / FG_XCDS * FG_XCDS));
-    hipLaunchKernelGGL((gemm_bf16_256<OutT, HAS_IN, A_KM, B_KM>), grid, dim3(FG_THREADS), 0, s, a);
+    hipLaunchKernelGGL((gemm_bf16_256<OutT, InT, A_KM, B_KM>), grid, dim3(FG_THREADS), 0, s, a);
     HIP_TRY(hipGetLastError());
     return FLCE_OK;
 }
@@ -185,13 +185,22 @@ int launch_ce_rows(T* Z, int64_t ldz, const int64_t* targets, int64_t rows, int6
         if (rc_ != FLCE_OK) return rc_; \
     } while (0)
 
+constexpr int MAX_HEADS = 16;   // headers of all heads share the 256-byte header slot
+static_assert(MAX_HEADS * sizeof(DeviceHeader) <= 256, "header slot too small");
+
+struct HeadWeights {
+    float w[MAX_HEADS];
+};
+
+// One head: count its valid rows, then run the chunk loop.  Gradients are scaled by
+// weight / N_valid.  With dx_add the head's dX is added to what dX already holds
+// (rounded to the storage type once per head), otherwise dX is overwritten.
 template <typename T>
-int run_fwd_bwd(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t H, int64_t V,
-                int64_t ignore_index, float* loss, T* dX, T* dW, unsigned flags, const Plan& p,
-                char* ws, hipStream_t s) {
+int run_head(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t H, int64_t V,
+             int64_t ignore_index, float weight, DeviceHeader* hdr, bool dx_add, T* dX, T* dW,
+             unsigned flags, const Plan& p, char* ws, hipStream_t s) {
     constexpr bool BF16 = (sizeof(T) == 2);
     const bool want_dx = !(flags & FLCE_SKIP_DX), want_dw = !(flags & FLCE_SKIP_DW);
-    DeviceHeader* hdr = reinterpret_cast<DeviceHeader*>(ws + p.off_hdr);
     float* row_loss = reinterpret_cast<float*>(ws + p.off_row_loss);
     T* Z = reinterpret_cast<T*>(ws + p.off_z);
     T* GT = reinterpret_cast<T*>(ws + p.off_gt);
@@ -200,7 +209,7 @@ int run_fwd_bwd(const T* X, const T* W, const int64_t* targets, int64_t BT, int6
     float* dWacc = reinterpret_cast<float*>(ws + p.off_dwacc);
 
     hipLaunchKernelGGL(count_valid_kernel, dim3(1), dim3(1024), 0, s, targets, BT, ignore_index,
-                       hdr);
+                       weight, hdr);
     HIP_TRY(hipGetLastError());
     if (want_dx && !p.fast_dx) FLCE_TRY(launch_transpose<T>(W, H, WT, p.ldz, V, H, s));   // WT[H x V]
 
@@ -214,7 +223,7 @@ int run_fwd_bwd(const T* X, const T* W, const int64_t* targets, int64_t BT, int6
         // logits of the chunk: Z = X_c W^T
         if (BF16 && p.fast_logits) {
             if constexpr (BF16)
-                FLCE_TRY((launch_gemm_fast<bf16_t, false, false, false>(
+                FLCE_TRY((launch_gemm_fast<bf16_t, void, false, false>(
                     FLCE_KIND_LOGITS_GEMM, Xc, H, W, H, Z, p.ldz, nullptr, 0, rows, V, H, s)));
         } else {
             FLCE_TRY((launch_gemm_generic<T, T>(FLCE_KIND_LOGITS_GEMM, Xc, H, W, H, Z, p.ldz, rows, V, H,
@@ -224,29 +233,36 @@ int run_fwd_bwd(const T* X, const T* W, const int64_t* targets, int64_t BT, int6
         // loss and in-place dlogits
         FLCE_TRY(launch_ce_rows<T>(Z, p.ldz, targets + r0, rows, V, ignore_index, hdr, row_loss, s));
 
-        // dX_c = G W
+        // dX_c (+)= G W
         if (want_dx) {
+            T* dXc = dX + r0 * H;
             if (BF16 && p.fast_dx) {
                 if constexpr (BF16) {
                     if (p.dx_ksplit > 1) {
                         // few output tiles, very long K: K ranges -> fp32 partials -> fixed-order sum
                         float* part = reinterpret_cast<float*>(ws + p.off_dxpart);
-                        FLCE_TRY((launch_gemm_fast<float, false, false, true>(
+                        FLCE_TRY((launch_gemm_fast<float, void, false, true>(
                             FLCE_KIND_DX_GEMM, Z, p.ldz, W, H, part, H, nullptr, 0, rows, H, V, s,
                             p.dx_ksplit, p.C * H)));
                         ScopedKernelTimer timer(FLCE_KIND_DX_GEMM, s);
-                        hipLaunchKernelGGL((splitk_reduce_kernel<bf16_t>), dim3(1024), dim3(256), 0, s,
-                                           part, p.C * H, p.dx_ksplit, dX + r0 * H, rows * H);
+                        if (dx_add)
+                            hipLaunchKernelGGL((splitk_reduce_kernel<bf16_t, true>), dim3(1024), dim3(256),
+                                               0, s, part, p.C * H, p.dx_ksplit, dXc, rows * H);
+                        else
+                            hipLaunchKernelGGL((splitk_reduce_kernel<bf16_t, false>), dim3(1024), dim3(256),
+                                               0, s, part, p.C * H, p.dx_ksplit, dXc, rows * H);
                         HIP_TRY(hipGetLastError());
+                    } else if (dx_add) {
+                        FLCE_TRY((launch_gemm_fast<bf16_t, bf16_t, false, true>(
+                            FLCE_KIND_DX_GEMM, Z, p.ldz, W, H, dXc, H, dXc, H, rows, H, V, s)));
                     } else {
-                        FLCE_TRY((launch_gemm_fast<bf16_t, false, false, true>(
-                            FLCE_KIND_DX_GEMM, Z, p.ldz, W, H, dX + r0 * H, H, nullptr, 0, rows, H, V,
-                            s)));
+                        FLCE_TRY((launch_gemm_fast<bf16_t, void, false, true>(
+                            FLCE_KIND_DX_GEMM, Z, p.ldz, W, H, dXc, H, nullptr, 0, rows, H, V, s)));
                     }
                 }
             } else {
-                FLCE_TRY((launch_gemm_generic<T, T>(FLCE_KIND_DX_GEMM, Z, p.ldz, WT, p.ldz, dX + r0 * H,
-                                                    H, rows, H, V, false, s)));
+                FLCE_TRY((launch_gemm_generic<T, T>(FLCE_KIND_DX_GEMM, Z, p.ldz, WT, p.ldz, dXc, H, rows,
+                                                    H, V, dx_add, s)));
             }
         }
 
@@ -256,16 +272,16 @@ int run_fwd_bwd(const T* X, const T* W, const int64_t* targets, int64_t BT, int6
             if (fast) {
                 if constexpr (BF16) {
                     if (p.nchunks == 1) {
-                        FLCE_TRY((launch_gemm_fast<bf16_t, false, true, true>(
+                        FLCE_TRY((launch_gemm_fast<bf16_t, void, true, true>(
                             FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dW, H, nullptr, 0, V, H, rows, s)));
                     } else if (c == 0) {
-                        FLCE_TRY((launch_gemm_fast<float, false, true, true>(
+                        FLCE_TRY((launch_gemm_fast<float, void, true, true>(
                             FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dWacc, H, nullptr, 0, V, H, rows, s)));
                     } else if (!last) {
-                        FLCE_TRY((launch_gemm_fast<float, true, true, true>(
+                        FLCE_TRY((launch_gemm_fast<float, float, true, true>(
                             FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dWacc, H, dWacc, H, V, H, rows, s)));
                     } else {   // last chunk: add the fp32 partial sums and write dW in bf16
-                        FLCE_TRY((launch_gemm_fast<bf16_t, true, true, true>(
+                        FLCE_TRY((launch_gemm_fast<bf16_t, float, true, true>(
                             FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dW, H, dWacc, H, V, H, rows, s)));
                     }
                 }
@@ -284,14 +300,34 @@ int run_fwd_bwd(const T* X, const T* W, const int64_t* targets, int64_t BT, int6
             }
         }
     }
-    hipLaunchKernelGGL(finalize_loss_kernel, dim3(1), dim3(64), 0, s, hdr, loss);
-    HIP_TRY(hipGetLastError());
     if (want_dw && dw_needs_cast) {
         ScopedKernelTimer timer(FLCE_KIND_OTHER, s);
         hipLaunchKernelGGL((cast_from_f32_kernel<T>), dim3(2048), dim3(256), 0, s, dWacc, dW,
                            V * H);
         HIP_TRY(hipGetLastError());
     }
+    return FLCE_OK;
+}
+
+// All heads one after the other on the same stream and the same workspace; then
+// loss = sum_j weight_j * mean loss of head j.
+template <typename T>
+int run_heads(const T* X, const void* const* W, const int64_t* const* targets, const float* weights,
+              int n_heads, int64_t BT, int64_t H, int64_t V, int64_t ignore_index, float* loss,
+              float* head_losses, T* dX, void* const* dW, unsigned flags, const Plan& p, char* ws,
+              hipStream_t s) {
+    DeviceHeader* hdr = reinterpret_cast<DeviceHeader*>(ws + p.off_hdr);
+    const bool want_dw = !(flags & FLCE_SKIP_DW);
+    HeadWeights hw{};
+    for (int j = 0; j < n_heads; ++j) {
+        hw.w[j] = weights ? weights[j] : 1.0f;
+        FLCE_TRY(run_head<T>(X, static_cast<const T*>(W[j]), targets[j], BT, H, V, ignore_index,
+                             hw.w[j], hdr + j, j > 0, dX, want_dw ? static_cast<T*>(dW[j]) : nullptr,
+                             flags, p, ws, s));
+    }
+    hipLaunchKernelGGL(finalize_loss_kernel, dim3(1), dim3(64), 0, s, hdr, n_heads, hw, loss,
+                       head_losses);
+    HIP_TRY(hipGetLastError());
     return FLCE_OK;
 }
 
@@ -306,16 +342,27 @@ int check_dims(int64_t BT, int64_t H, int64_t V, int dtype) {
 
 extern "C" {
 
-int flce_fwd_bwd_ex(const void* X, const void* W, const int64_t* targets, int64_t BT, int64_t H,
-                    int64_t V, int64_t ignore_index, int dtype, float* loss, void* dX, void* dW,
-                    unsigned flags, void* stream) {
+int flce_multihead_fwd_bwd(const void* X, const void* const* W, const int64_t* const* targets,
+                           const float* weights, int n_heads, int64_t BT, int64_t H, int64_t V,
+                           int64_t ignore_index, int dtype, float* loss, float* head_losses, void* dX,
+                           void* const* dW, unsigned flags, void* stream) {
     FLCE_TRY(check_dims(BT, H, V, dtype));
+    if (n_heads < 1 || n_heads > MAX_HEADS) return FLCE_ERR_ARG;
     if (flags & ~(unsigned)(FLCE_SKIP_DX | FLCE_SKIP_DW)) return FLCE_ERR_ARG;
     const bool want_dx = !(flags & FLCE_SKIP_DX), want_dw = !(flags & FLCE_SKIP_DW);
     if (!X || !W || !targets || !loss || (want_dx && !dX) || (want_dw && !dW)) return FLCE_ERR_NULL;
-    if (!aligned(X, 16) || !aligned(W, 16) || (want_dx && !aligned(dX, 16)) ||
-        (want_dw && !aligned(dW, 16)) || !aligned(targets, 8) || !aligned(loss, 4))
+    if (!aligned(X, 16) || (want_dx && !aligned(dX, 16)) || !aligned(loss, 4) ||
+        (head_losses && !aligned(head_losses, 4)))
         return FLCE_ERR_ALIGN;
+    for (int j = 0; j < n_heads; ++j) {
+        if (!W[j] || !targets[j] || (want_dw && !dW[j])) return FLCE_ERR_NULL;
+        if (!aligned(W[j], 16) || !aligned(targets[j], 8) || (want_dw && !aligned(dW[j], 16)))
+            return FLCE_ERR_ALIGN;
+        if (weights && !(weights[j] == weights[j] && weights[j] - weights[j] == 0.0f))
+            return FLCE_ERR_ARG;   // NaN or infinite weight
+        for (int k = 0; want_dw && k < j; ++k)
+            if (dW[k] == dW[j]) return FLCE_ERR_ARG;   // every head needs a dW of its own
+    }
     if (ignore_index >= 0 && ignore_index < V) return FLCE_ERR_ARG;   // would shadow a class
 
     const Plan p = make_plan(BT, H, V, dtype, g_budget);
@@ -323,12 +370,22 @@ int flce_fwd_bwd_ex(const void* X, const void* W, const int64_t* targets, int64_
     FLCE_TRY(acquire_workspace(p.total, &ws));
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (dtype == FLCE_F32)
-        return run_fwd_bwd<float>(static_cast<const float*>(X), static_cast<const float*>(W),
-                                  targets, BT, H, V, ignore_index, loss, static_cast<float*>(dX),
-                                  static_cast<float*>(dW), flags, p, ws, s);
-    return run_fwd_bwd<bf16_t>(static_cast<const bf16_t*>(X), static_cast<const bf16_t*>(W),
-                               targets, BT, H, V, ignore_index, loss, static_cast<bf16_t*>(dX),
-                               static_cast<bf16_t*>(dW), flags, p, ws, s);
+        return run_heads<float>(static_cast<const float*>(X), W, targets, weights, n_heads, BT, H, V,
+                                ignore_index, loss, head_losses, static_cast<float*>(dX), dW, flags,
+                                p, ws, s);
+    return run_heads<bf16_t>(static_cast<const bf16_t*>(X), W, targets, weights, n_heads, BT, H, V,
+                             ignore_index, loss, head_losses, static_cast<bf16_t*>(dX), dW, flags, p,
+                             ws, s);
+}
+
+int flce_fwd_bwd_ex(const void* X, const void* W, const int64_t* targets, int64_t BT, int64_t H,
+                    int64_t V, int64_t ignore_index, int dtype, float* loss, void* dX, void* dW,
+                    unsigned flags, void* stream) {
+    const void* Ws[1] = {W};
+    const int64_t* ts[1] = {targets};
+    void* dWs[1] = {dW};
+    return flce_multihead_fwd_bwd(X, Ws, ts, nullptr, 1, BT, H, V, ignore_index, dtype, loss, nullptr,
+                                  dX, dWs, flags, stream);
 }
 
 int flce_fwd_bwd(const void* X, const void* W, const int64_t* targets, int64_t BT, int64_t H,
@@ -352,7 +409,7 @@ int flce_cross_entropy_inplace(void* Z, const int64_t* targets, int64_t BT, int6
     float* row_loss = reinterpret_cast<float*>(ws + 256);
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(count_valid_kernel, dim3(1), dim3(1024), 0, s, targets, BT, ignore_index,
-                       hdr);
+                       1.0f, hdr);
     HIP_TRY(hipGetLastError());
     for (int64_t r0 = 0; r0 < BT; r0 += step) {
         const int64_t rows = (BT - r0 < step) ? BT - r0 : step;
@@ -363,7 +420,10 @@ int flce_cross_entropy_inplace(void* Z, const int64_t* targets, int64_t BT, int6
             FLCE_TRY(launch_ce_rows<bf16_t>(static_cast<bf16_t*>(Z) + r0 * ldz, ldz, targets + r0,
                                             rows, V, ignore_index, hdr, row_loss, s));
     }
-    hipLaunchKernelGGL(finalize_loss_kernel, dim3(1), dim3(64), 0, s, hdr, loss);
+    HeadWeights one{};
+    one.w[0] = 1.0f;
+    hipLaunchKernelGGL(finalize_loss_kernel, dim3(1), dim3(64), 0, s, hdr, 1, one, loss,
+                       static_cast<float*>(nullptr));
     HIP_TRY(hipGetLastError());
     return FLCE_OK;
 }

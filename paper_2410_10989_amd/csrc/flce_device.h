@@ -47,7 +47,7 @@ __device__ __forceinline__ int wave_sum(int v) {
 // consumed on the device, so the host never waits for them.
 struct DeviceHeader {
     int32_t n_valid;   // rows whose target is not ignore_index
-    float inv_n;       // 1 / n_valid, or 0 when n_valid == 0
+    float inv_n;       // weight / n_valid (weight = 1 for a single head), 0 when n_valid == 0
     double loss_sum;   // running sum of per-row losses
 };
 

@@ -1,6 +1,6 @@
 // Tuned bf16 matrix product for gfx950, fp32 accumulation on
 // v_mfma_f32_32x32x16_bf16:
-//     C[M x N] = (Cin +) sum_k a(m,k) * b(n,k)
+//     C[M x N] = (Cin +) sum_k a(m,k) * b(n,k)          (Cin: fp32 or bf16, optional)
 // where each operand is given either K-contiguous ("row" form: a(m,k) = A[m*lda + k])
 // or K-major ("column" form: a(m,k) = A[k*lda + m]).  All three products of the
 // fused linear cross-entropy path run on it without transposed copies:
@@ -73,7 +73,7 @@ struct FGArgs {
     int64_t ldb;
     void* C;
     int64_t ldc;
-    const float* Cin;   // optional fp32 addend (may alias C when C is fp32)
+    const void* Cin;    // optional addend, fp32 or bf16 (may alias C when of C's type)
     int64_t ldcin;
     int M, N, K;
     int tiles_m, tiles_n;
@@ -250,8 +250,14 @@ __device__ __forceinline__ void fg_zero(FgRaw<true>& r) {
     }
 }
 
-template <typename OutT, bool HAS_IN, bool A_KM, bool B_KM>
+template <typename InT> struct FgInSize { static constexpr int value = (int)sizeof(InT); };
+template <> struct FgInSize<void> { static constexpr int value = 4; };
+
+// InT: element type of the addend Cin (float or bf16_t), void for no addend.
+template <typename OutT, typename InT, bool A_KM, bool B_KM>
 __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
+    constexpr bool HAS_IN = !std::is_void<InT>::value;
+    constexpr int IS = FgInSize<InT>::value;
     __shared__ __attribute__((aligned(16))) unsigned char smem[FG_LDS_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -429,10 +435,11 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
                      (uint32_t)rows_c * (uint32_t)ldc * (uint32_t)ES);
     __amdgpu_buffer_rsrc_t rsrc_in = rsrc_c;
     if constexpr (HAS_IN)
-        rsrc_in = fg_make_rsrc(a.Cin + (int64_t)m0 * a.ldcin, (uint32_t)rows_c * (uint32_t)ldcin * 4u);
+        rsrc_in = fg_make_rsrc(static_cast<const unsigned char*>(a.Cin) + (int64_t)m0 * a.ldcin * IS,
+                               (uint32_t)rows_c * (uint32_t)ldcin * (uint32_t)IS);
     const int uwm = __builtin_amdgcn_readfirstlane(wm), uwn = __builtin_amdgcn_readfirstlane(wn);
     const int lane_off = (4 * fhalf * ldc + frow) * ES;
-    const int lane_off_in = (4 * fhalf * ldcin + frow) * 4;
+    const int lane_off_in = (4 * fhalf * ldcin + frow) * IS;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int col0 = n0 + uwn * 128 + j * 32;
@@ -444,9 +451,14 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
                     float old[16];
 #pragma unroll
                     for (int g = 0; g < 16; ++g) {
-                        const int soff = ((row0 + 8 * (g >> 2) + (g & 3)) * ldcin + col0) * 4;
-                        old[g] = __uint_as_float(
-                            __builtin_amdgcn_raw_buffer_load_b32(rsrc_in, lane_off_in, soff, 0));
+                        const int soff = ((row0 + 8 * (g >> 2) + (g & 3)) * ldcin + col0) * IS;
+                        if constexpr (IS == 4)
+                            old[g] = __uint_as_float(
+                                __builtin_amdgcn_raw_buffer_load_b32(rsrc_in, lane_off_in, soff, 0));
+                        else   // bf16 addend: its 16 bits are the high half of the float
+                            old[g] = __uint_as_float(
+                                (unsigned)__builtin_amdgcn_raw_buffer_load_b16(rsrc_in, lane_off_in, soff, 0)
+                                << 16);
                     }
 #pragma unroll
                     for (int g = 0; g < 16; ++g) acc[i][j][g] += old[g];

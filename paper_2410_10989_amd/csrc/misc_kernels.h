@@ -27,12 +27,14 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ in
 
 // out[r][c] = sum_s part[s][r][c] in the fixed order s = 0, 1, ...: the reduction
 // of split-K partial results (row stride ld for both).
-template <typename T>
+// With ADD the previous content of out is added as well (dX summed over heads).
+template <typename T, bool ADD>
 __global__ void splitk_reduce_kernel(const float* __restrict__ part, int64_t split_stride, int nsplit,
                                      T* __restrict__ out, int64_t n) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
          i += (int64_t)gridDim.x * blockDim.x) {
         float v = part[i];
+        if constexpr (ADD) v += to_f32(out[i]);
         for (int s = 1; s < nsplit; ++s) v += part[(int64_t)s * split_stride + i];
         out[i] = from_f32<T>(v);
     }

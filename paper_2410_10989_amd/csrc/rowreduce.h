@@ -220,9 +220,10 @@ __global__ __launch_bounds__(256) void loss_accumulate_kernel(const float* __res
 }
 
 // Counts the valid rows and resets the running loss.  Integer sum: exact in any order.
+// `weight` scales every gradient of this head (1 for a single head).
 __global__ __launch_bounds__(1024) void count_valid_kernel(const int64_t* __restrict__ targets,
                                                            int64_t BT, int64_t ignore_index,
-                                                           DeviceHeader* hdr) {
+                                                           float weight, DeviceHeader* hdr) {
     __shared__ int part[16];
     int c = 0;
     for (int64_t i = threadIdx.x; i < BT; i += 1024) c += (targets[i] != ignore_index);
@@ -233,14 +234,27 @@ __global__ __launch_bounds__(1024) void count_valid_kernel(const int64_t* __rest
         int n = 0;
         for (int w = 0; w < 16; ++w) n += part[w];
         hdr->n_valid = n;
-        hdr->inv_n = n > 0 ? 1.0f / (float)n : 0.f;
+        hdr->inv_n = n > 0 ? weight / (float)n : 0.f;
         hdr->loss_sum = 0.0;
     }
 }
 
-__global__ void finalize_loss_kernel(const DeviceHeader* hdr, float* loss) {
-    if (threadIdx.x == 0 && blockIdx.x == 0)
-        *loss = hdr->n_valid > 0 ? (float)(hdr->loss_sum / (double)hdr->n_valid) : 0.f;
+// loss = sum over heads of weight_j * (mean loss of head j); head_losses (optional)
+// receives the unweighted means.  One header per head; WeightsT is a struct of
+// floats w[] passed by value.
+template <typename WeightsT>
+__global__ void finalize_loss_kernel(const DeviceHeader* hdr, int n_heads, WeightsT weights,
+                                     float* loss, float* __restrict__ head_losses) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        double total = 0.0;
+        for (int j = 0; j < n_heads; ++j) {
+            const double mean =
+                hdr[j].n_valid > 0 ? hdr[j].loss_sum / (double)hdr[j].n_valid : 0.0;
+            if (head_losses) head_losses[j] = (float)mean;
+            total += (double)weights.w[j] * mean;
+        }
+        *loss = (float)total;
+    }
 }
 
 }  // namespace flce

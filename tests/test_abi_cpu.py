@@ -86,6 +86,21 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert call(ign=3) == 7
     assert L.flce_fwd_bwd_ex(ok["X"], ok["W"], ok["t"], 4, 8, 16, -100, 1, ok["loss"], None, None,
                              64, None) == 7
+    # several heads: host arrays of device pointers
+    P2 = ctypes.c_void_p * 2
+    Ws, ts, dWs = P2(a + 256, a + 1536), P2(a + 512, a + 512), P2(a + 1280, a + 1792)
+
+    def heads(n=2, W=Ws, t=ts, dW=dWs, wts=None, flags=0):
+        return L.flce_multihead_fwd_bwd(a, W, t, wts, n, 4, 8, 16, -100, 1, a + 768, None, a + 1024,
+                                        dW, flags, None)
+
+    F2 = ctypes.c_float * 2
+    assert heads(n=0) == 7 and heads(n=17) == 7
+    assert heads(W=P2(a + 256, None)) == 1 and heads(dW=None) == 1 and heads(t=None) == 1
+    assert heads(dW=P2(a + 1280, a + 1280)) == 7              # heads sharing one dW
+    assert heads(wts=F2(1.0, float("nan"))) == 7 and heads(wts=F2(float("inf"), 1.0)) == 7
+    assert heads(W=P2(a + 256, a + 1538)) == 4
+    assert heads(flags=8) == 7
     assert L.flce_set_logits_budget_bytes(0) == 7
     assert L.flce_cross_entropy_inplace(None, a, 1, 1, 1, -100, 1, a, None) == 1
     assert L.flce_cross_entropy_inplace(a, a, 4, 16, 8, -100, 1, a, None) == 2   # ldz < V

@@ -228,3 +228,72 @@ def test_brute_force_single_row_by_hand():
     np.testing.assert_allclose(r.dX[0], dX, atol=1e-16)
     for v in range(3):
         np.testing.assert_allclose(r.dW[v], [g[v] * 1.0, g[v] * -2.0], atol=1e-16)
+
+
+# ---- several heads on shared hidden states (paper section 4.2, Medusa paragraph) ----
+
+def _heads_case(n=3, BT=24, H=6, V=11, seq=8, seed=5):
+    g = np.random.default_rng(seed)
+    X = g.standard_normal((BT, H))
+    Ws = [g.standard_normal((V, H)) * 0.6 for _ in range(n)]
+    base = g.integers(0, V, size=BT).astype(np.int64)
+    base[3] = IGN
+    ts = [base]
+    for j in range(1, n):       # head j looks j tokens further inside its sequence
+        t = np.full(BT, IGN, dtype=np.int64)
+        for s in range(0, BT, seq):
+            t[s:s + seq - j] = base[s + j:s + seq]
+        ts.append(t)
+    return X, Ws, ts, [1.0, 0.8, 0.64][:n]
+
+
+def test_multihead_matches_autograd_of_the_weighted_sum_of_library_losses():
+    # dX must collect every head's contribution with its weight, dW_j only head
+    # j's; each head divides by ITS OWN number of valid rows.
+    X, Ws, ts, wts = _heads_case()
+    r = oracle.flce_multihead(X, Ws, ts, wts, IGN)
+    Xt = torch.tensor(X, requires_grad=True)
+    Wt = [torch.tensor(W, requires_grad=True) for W in Ws]
+    per_head = [torch.nn.functional.cross_entropy(Xt @ W.T, torch.tensor(t), ignore_index=IGN)
+                for W, t in zip(Wt, ts)]
+    total = sum(w * l for w, l in zip(wts, per_head))
+    total.backward()
+    assert abs(r.loss - total.item()) <= 1e-13 * abs(total.item())
+    for mine, ref in zip(r.head_losses, per_head):
+        assert abs(mine - ref.item()) <= 1e-13 * abs(ref.item())
+    np.testing.assert_allclose(r.dX, Xt.grad.numpy(), rtol=0, atol=1e-14)
+    for mine, ref in zip(r.dWs, Wt):
+        np.testing.assert_allclose(mine, ref.grad.numpy(), rtol=0, atol=1e-14)
+    # the heads see different numbers of valid rows, so a shared divisor would show
+    assert len({int((t != IGN).sum()) for t in ts}) == len(ts)
+
+
+def test_multihead_with_one_head_is_the_single_head_result():
+    X, Ws, ts, _ = _heads_case(n=1)
+    r1 = oracle.flce_multihead(X, Ws, ts, None, IGN)
+    r0 = oracle.flce(X, Ws[0], ts[0], IGN)
+    assert r1.loss == r0.loss and r1.head_losses == [r0.loss]
+    assert np.array_equal(r1.dX, r0.dX) and np.array_equal(r1.dWs[0], r0.dW)
+
+
+def test_multihead_same_head_twice_doubles_loss_and_dX_but_not_dW():
+    X, Ws, ts, _ = _heads_case(n=1)
+    r0 = oracle.flce(X, Ws[0], ts[0], IGN)
+    r2 = oracle.flce_multihead(X, [Ws[0], Ws[0].copy()], [ts[0], ts[0]], None, IGN)
+    assert abs(r2.loss - 2 * r0.loss) <= 1e-15 * abs(r0.loss)
+    np.testing.assert_allclose(r2.dX, 2 * r0.dX, rtol=0, atol=1e-16)
+    for d in r2.dWs:
+        np.testing.assert_allclose(d, r0.dW, rtol=0, atol=0)
+
+
+def test_multihead_workload_shifts_targets_inside_sequences():
+    m = workloads.make_multihead(3, BT=40, H=8, V=50, seq=16, dtype="f32", seed=9)
+    t0 = m.targets[0]
+    for j in (1, 2):
+        tj = m.targets[j]
+        for s in range(0, 40, 16):
+            e = min(s + 16, 40)
+            assert (tj[e - j:e] == IGN).all()
+            assert np.array_equal(tj[s:e - j], t0[s + j:e])
+    assert m.weights == [1.0, 0.8, 0.8 ** 2]
+    assert not np.array_equal(m.Ws[1], m.Ws[2]) and m.Ws[0] is m.base.W

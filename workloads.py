@@ -141,6 +141,38 @@ def make(BT, H, V, dtype="bf16", targets="uniform", ignore=("none",), seed=BASE_
     return Workload(name, BT, H, V, dtype, X, W, t, ignore_index, seed)
 
 
+@dataclass
+class MultiHeadWorkload:
+    base: Workload                     # X, head 0's W and targets
+    Ws: list                           # n_heads weights [V, H]
+    targets: list                      # n_heads int64 [BT]
+    weights: list                      # n_heads floats
+
+
+def make_multihead(n_heads, BT, H, V, seq, dtype="bf16", targets="uniform", ignore=("none",),
+                   seed=BASE_SEED, decay=0.8, **kw) -> MultiHeadWorkload:
+    """Inputs for several decoding heads on shared hidden states.
+
+    The rows are sequences of `seq` tokens.  Head 0 has the base workload's
+    targets; head j looks j positions further on inside the same sequence (its
+    target at position t is head 0's target at t + j) and ignores the last j
+    positions of every sequence.  Each head has its own weight (tensor ids
+    16 + j); head j's loss weight is decay**j.
+    """
+    base = make(BT, H, V, dtype, targets, ignore, seed, name=f"multihead{n_heads}", **kw)
+    Ws, ts = [base.W], [base.targets]
+    w_std = kw.get("w_std", 0.02)
+    for j in range(1, n_heads):
+        Ws.append(_normal(seed, 16 + j, (V, H), w_std, dtype))
+        t = np.full(BT, base.ignore_index, dtype=np.int64)
+        for s in range(0, BT, seq):
+            e = min(s + seq, BT)
+            if e - s > j:
+                t[s:e - j] = base.targets[s + j:e]
+        ts.append(t)
+    return MultiHeadWorkload(base, Ws, ts, [float(decay) ** j for j in range(n_heads)])
+
+
 def make_config(index: int, BT: int | None = None) -> Workload:
     """Workload `index` (1-based, the order of the benchmark's config list).
     `BT` overrides the row count (used for bounded samples and BT sweeps)."""
