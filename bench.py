@@ -93,6 +93,11 @@ def main():
     ap.add_argument("--mode", choices=("flce", "ce"), default="flce",
                     help="flce: the fused path (default); ce: stand-alone cross entropy on given "
                          "logits, swept over the vocabulary sizes of the paper's kernel benchmark")
+    ap.add_argument("--heads", type=int, default=1,
+                    help="> 1: that many decoding heads on the shared hidden states (the paper's "
+                         "Medusa setting, section 4.2), timed through flce_multihead_fwd_bwd")
+    ap.add_argument("--skip-dx", action="store_true",
+                    help="frozen backbone (Medusa stage 1): no hidden-state gradient")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one plain 1 GiB device copy first (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -137,8 +142,31 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    def step():
-        flce.flce_fwd_bwd(X, W, t, w.ignore_index, loss=loss, dX=dX, dW=dW)
+    nh = args.heads
+    flags = flce.SKIP_DX if args.skip_dx else 0
+    if nh > 1:
+        # extra heads: seeded N(0, 0.02^2) weights drawn on the device; head j's target at
+        # position p is head 0's target at p + j inside sequences of 2048 tokens
+        seq = 2048
+        Ws, ts, dWs = [W], [t], [dW]
+        pos = torch.arange(w.BT, device="cuda") % seq
+        for j in range(1, nh):
+            g = torch.Generator(device="cuda").manual_seed(w.seed + 16 + j)
+            Ws.append((torch.randn(w.V, w.H, generator=g, device="cuda") * 0.02).to(tdt))
+            tj = torch.roll(t, -j)
+            tj[pos >= seq - j] = w.ignore_index
+            ts.append(tj)
+            dWs.append(torch.empty_like(W))
+        wts = [0.8 ** j for j in range(nh)]
+        hl = torch.empty(nh, dtype=torch.float32, device="cuda")
+
+        def step():
+            flce.flce_multihead_fwd_bwd(X, Ws, ts, wts, w.ignore_index, loss=loss, head_losses=hl,
+                                        dX=None if args.skip_dx else dX, dWs=dWs, flags=flags)
+    else:
+        def step():
+            flce.flce_fwd_bwd(X, W, t, w.ignore_index, loss=loss, dX=None if args.skip_dx else dX,
+                              dW=dW, flags=flags)
 
     for _ in range(args.warmup):
         step()
@@ -156,7 +184,7 @@ def main():
     ms_per_step = (t2 - t1) * 1e3 / args.steps
     tokens_per_s = w.BT / (ms_per_step * 1e-3)
 
-    flops_step = 6.0 * w.BT * w.H * w.V
+    flops_step = (4.0 if args.skip_dx else 6.0) * w.BT * w.H * w.V * nh
     tflops = flops_step / (ms_per_step * 1e-3) / 1e12
     peak = MFMA_PEAK_TFLOPS[w.dtype]
 
@@ -164,18 +192,19 @@ def main():
     # dX products are one symbol each; with several chunks the dW product runs as
     # two symbols (fp32 partial sums, then the bf16 result), so its time is split.
     nchunks = flce.flce_num_chunks(w.BT, w.H, w.V, code)
-    gemm_kinds = ("logits_gemm", "dx_gemm", "dw_gemm")
+    gemm_kinds = ("logits_gemm", "dw_gemm") if args.skip_dx else ("logits_gemm", "dx_gemm", "dw_gemm")
     symbols = {"logits_gemm": 1, "dx_gemm": 1, "dw_gemm": 2 if nchunks > 1 else 1}
     dom = max(gemm_kinds, key=lambda k: kt[k][0] / symbols[k])
     dom_ms, dom_n = kt[dom]
-    flops_per_launch = 2.0 * w.BT * w.H * w.V * args.steps / max(dom_n, 1)   # mean over its launches
+    flops_per_launch = 2.0 * w.BT * w.H * w.V * nh * args.steps / max(dom_n, 1)   # mean over its launches
     dom_avg_ms = dom_ms / max(dom_n, 1)
     achieved = flops_per_launch / (dom_avg_ms * 1e-3) / 1e12 if dom_n else 0.0
     ce_ms, ce_n = kt["ce_rows"]
     ce_gbs = (2.0 * w.BT * w.V * (2 if w.dtype == "bf16" else 4) * args.steps) / (ce_ms * 1e-3) / 1e9 if ce_n else 0.0
 
     out = {
-        "metric": "FLCE fwd+bwd tokens/s",
+        "metric": "FLCE fwd+bwd tokens/s" if nh == 1 and not args.skip_dx else
+                  f"FLCE fwd+bwd tokens/s, {nh} head(s)" + (", no dX" if args.skip_dx else ""),
         "value": tokens_per_s,
         "unit": "tokens/s",
         "n_gpus": 1,
@@ -191,7 +220,8 @@ def main():
                    "ignore_frac": round(1 - w.n_valid / w.BT, 4), "chunk_rows":
                    flce.flce_chunk_rows(w.BT, w.H, w.V, code), "chunks": nchunks,
                    "logits_budget_mib": flce.flce_get_logits_budget_bytes() >> 20},
-        "tflops_over_6BTHV": tflops,
+        "heads": nh,
+        "tflops_over_6BTHV": tflops,   # over 6*BT*H*V per head (4*BT*H*V without dX)
         "mfma_util_frac_of_peak": tflops / peak,
         "peak_extra_hbm_mb": flce.flce_workspace_bytes(w.BT, w.H, w.V, code) / 1e6,
         "full_logits_avoided_mb": flce.flce_full_logits_bytes(w.BT, w.V, code) / 1e6,
@@ -202,7 +232,8 @@ def main():
                      "unit": "TFLOP/s", "frac": achieved / peak,
                      "avg_launch_ms": dom_avg_ms, "launches": dom_n,
                      "flops_per_launch": flops_per_launch,
-                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH if args.config == 3 else None},
+                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH
+                     if args.config == 3 and dom == "logits_gemm" and not args.budget_mib else None},
     }
 
     if not args.no_cpu_baseline:
@@ -210,7 +241,7 @@ def main():
         n = min(args.cpu_sample_rows, w.BT)
         tc = time.perf_counter()
         flce_oracle.flce(w.X[:n], w.W, w.targets[:n], w.ignore_index)
-        dt = time.perf_counter() - tc
+        dt = (time.perf_counter() - tc) * nh    # every head costs the oracle the same again
         out["cpu_baseline"] = {"value": n / dt, "unit": "tokens/s", "cores": flce_oracle.threads(),
                                "kind": "oracle",
                                "sample": f"first {n} of {w.BT} rows of the same workload, full fp64 "
