@@ -127,6 +127,31 @@ FLCE_API int flce_multihead_fwd_bwd(const void* X, const void* const* W, const i
                            void* dX, void* const* dW, unsigned flags, void* stream);
 
 /*
+ * RMSNorm in front of the projection, fused into the same call (paper section
+ * 3.2, RMSNorm paragraph, Eq. RMSNorm-forward / RMSNorm-backward, followed by
+ * the FLCE paragraph).  For raw hidden states h[BT x H] and a scale gamma[H]:
+ *
+ *     x_i    = h_i / sqrt(mean_j h_ij^2 + eps) * gamma        (row by row)
+ *     loss, dW as flce_fwd_bwd on X = x
+ *     dh     = gradient of the loss w.r.t. h      dgamma = gradient w.r.t. gamma
+ *
+ * The normalised rows and their gradient exist only one chunk at a time in the
+ * workspace, so peak extra memory stays independent of BT.  x is rounded to
+ * dtype once (after the multiplication by gamma) before it enters the products.
+ *   h, dh        device, [BT x H] dtype     in / out
+ *   gamma,dgamma device, [H] dtype          in / out
+ *   eps          finite, >= 0
+ *   flags        FLCE_SKIP_DX: neither dh nor dgamma is computed (both may be
+ *                NULL); FLCE_SKIP_DW: dW may be NULL
+ * Everything else as flce_fwd_bwd.
+ */
+FLCE_API int flce_rmsnorm_fwd_bwd(const void* h, const void* gamma, float eps, const void* W,
+                         const int64_t* targets, int64_t BT, int64_t H, int64_t V,
+                         int64_t ignore_index, int dtype, float* loss, void* dh, void* dgamma,
+                         void* dW, unsigned flags, void* stream);
+FLCE_API size_t flce_rmsnorm_workspace_bytes(int64_t BT, int64_t H, int64_t V, int dtype);
+
+/*
  * Stand-alone cross entropy on given logits (paper section 3.2, CE paragraph):
  * Z[BT x V] (device, dtype, row stride ldz elements, ldz >= V) is replaced in
  * place by dL/dZ; loss receives the mean over valid rows.  Needs no workspace

@@ -136,6 +136,39 @@ def flce_multihead(X, Ws, targets, weights=None, ignore_index=-100, want_dX=True
     return MultiHeadResult(total, head_losses, dX, dWs)
 
 
+@dataclass
+class RmsNormResult:
+    loss: float
+    y: np.ndarray              # [BT, H] normalised, scaled hidden states
+    dh: np.ndarray | None      # [BT, H]
+    dgamma: np.ndarray | None  # [H]
+    dW: np.ndarray | None      # [V, H]
+
+
+def rmsnorm_flce(h, gamma, eps, W, targets, ignore_index=-100, want_dh=True,
+                 want_dW=True) -> RmsNormResult:
+    """RMSNorm (paper section 3.2, RMSNorm paragraph) followed by the projection
+    and cross entropy.  Forward, row by row: RMS = sqrt(sum_j h_j^2 / n + eps),
+    xhat = h / RMS, y = xhat * gamma.  Backward with g = dL/dy:
+    dh = (g*gamma - [xhat . (g*gamma) / n] xhat) / RMS, dgamma = sum over rows of
+    g * xhat.  g is the dX of the linear cross-entropy oracle evaluated at X = y."""
+    h = np.asarray(h, dtype=np.float64)
+    gamma = np.asarray(gamma, dtype=np.float64)
+    n = h.shape[1]
+    rms = np.sqrt((h * h).sum(axis=1) / n + eps)
+    xhat = h / rms[:, None]
+    y = xhat * gamma[None, :]
+    r = flce(y, np.asarray(W, dtype=np.float64), targets, ignore_index, want_dX=want_dh,
+             want_dW=want_dW)
+    dh = dgamma = None
+    if want_dh:
+        gg = r.dX * gamma[None, :]
+        inner = (xhat * gg).sum(axis=1) / n
+        dh = (gg - inner[:, None] * xhat) / rms[:, None]
+        dgamma = (r.dX * xhat).sum(axis=0)
+    return RmsNormResult(r.loss, y, dh, dgamma, r.dW)
+
+
 def cross_entropy(Z, targets, ignore_index=-100):
     """Stand-alone CE on given logits Z [BT, V] (fp64): (loss, dlogits, lse)."""
     lib = _load()

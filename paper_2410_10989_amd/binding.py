@@ -38,6 +38,8 @@ def lib() -> ctypes.CDLL:
             "flce_fwd_bwd": ([p, p, p, i64, i64, i64, i64, ci, p, p, p, p], ci),
             "flce_fwd_bwd_ex": ([p, p, p, i64, i64, i64, i64, ci, p, p, p, u, p], ci),
             "flce_multihead_fwd_bwd": ([p, p, p, p, ci, i64, i64, i64, i64, ci, p, p, p, p, u, p], ci),
+            "flce_rmsnorm_fwd_bwd": ([p, p, ctypes.c_float, p, p, i64, i64, i64, i64, ci, p, p, p, p, u, p], ci),
+            "flce_rmsnorm_workspace_bytes": ([i64, i64, i64, ci], sz),
             "flce_cross_entropy_inplace": ([p, p, i64, i64, i64, i64, ci, p, p], ci),
             "flce_workspace_bytes": ([i64, i64, i64, ci], sz),
             "flce_workspace_bytes_max": ([i64, i64, ci], sz),
@@ -174,6 +176,43 @@ def flce_multihead_fwd_bwd(X, Ws, targets, weights=None, ignore_index=-100, loss
                                           dw_arr, int(flags), _stream_handle(stream))
     _check(st, "flce_multihead_fwd_bwd")
     return loss, head_losses, dX, dWs
+
+
+def flce_rmsnorm_fwd_bwd(h, gamma, eps, W, targets, ignore_index=-100, loss=None, dh=None,
+                         dgamma=None, dW=None, flags=0, stream=None):
+    """loss, dh, dgamma, dW of mean cross_entropy(rmsnorm(h; gamma, eps) @ W.T, targets)."""
+    code = _dtype_code(h)
+    if W.dtype != h.dtype or gamma.dtype != h.dtype:
+        raise TypeError("h, gamma and W must have the same dtype")
+    if h.dim() != 2 or W.dim() != 2 or h.shape[1] != W.shape[1] or gamma.shape != (h.shape[1],) \
+            or targets.shape != (h.shape[0],):
+        raise ValueError("expected h [BT, H], gamma [H], W [V, H], targets [BT]")
+    if targets.dtype != torch.int64:
+        raise TypeError("targets must be int64")
+    BT, H = h.shape
+    V = W.shape[0]
+    if loss is None:
+        loss = torch.empty((), dtype=torch.float32, device=h.device)
+    if not (flags & SKIP_DX):
+        dh = torch.empty_like(h) if dh is None else dh
+        dgamma = torch.empty_like(gamma) if dgamma is None else dgamma
+    if dW is None and not (flags & SKIP_DW):
+        dW = torch.empty_like(W)
+    for name, t, ref in (("dh", dh, h), ("dgamma", dgamma, gamma), ("dW", dW, W)):
+        if t is not None and (t.shape != ref.shape or t.dtype != ref.dtype):
+            raise ValueError(f"{name} must match its input in shape and dtype")
+    with torch.cuda.device(h.device):
+        st = lib().flce_rmsnorm_fwd_bwd(_dev_ptr(h, "h"), _dev_ptr(gamma, "gamma"), float(eps),
+                                        _dev_ptr(W, "W"), _dev_ptr(targets, "targets"), BT, H, V,
+                                        int(ignore_index), code, _dev_ptr(loss, "loss"),
+                                        _dev_ptr(dh, "dh"), _dev_ptr(dgamma, "dgamma"),
+                                        _dev_ptr(dW, "dW"), int(flags), _stream_handle(stream))
+    _check(st, "flce_rmsnorm_fwd_bwd")
+    return loss, dh, dgamma, dW
+
+
+def flce_rmsnorm_workspace_bytes(BT, H, V, dtype) -> int:
+    return int(lib().flce_rmsnorm_workspace_bytes(BT, H, V, _DTYPES.get(dtype, dtype)))
 
 
 def flce_cross_entropy_inplace(Z, targets, ignore_index=-100, loss=None, stream=None):

@@ -10,6 +10,7 @@
 #include "gemm_bf16_nt.h"
 #include "gemm_generic.h"
 #include "misc_kernels.h"
+#include "rmsnorm.h"
 #include "rowreduce.h"
 #include "scheduler.h"
 
@@ -192,13 +193,28 @@ struct HeadWeights {
     float w[MAX_HEADS];
 };
 
+// RMSNorm in front of the projection: the chunk loop normalises each chunk of the
+// raw hidden states into Y just before its logits product and turns the chunk's
+// dX (left in dY) into the gradient of the raw hidden states right after.
+template <typename T>
+struct NormCtx {
+    const T* gamma;
+    float eps;
+    T* Y;            // [C x H] normalised chunk
+    T* dY;           // [C x H] gradient w.r.t. the normalised chunk
+    float* rstd;     // [C]
+    float* partial;  // [RN_SLOTS x H] fp32 partial sums of dgamma, zero before the loop
+    T* dh;           // [BT x H] out
+};
+
 // One head: count its valid rows, then run the chunk loop.  Gradients are scaled by
 // weight / N_valid.  With dx_add the head's dX is added to what dX already holds
 // (rounded to the storage type once per head), otherwise dX is overwritten.
 template <typename T>
 int run_head(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t H, int64_t V,
              int64_t ignore_index, float weight, DeviceHeader* hdr, bool dx_add, T* dX, T* dW,
-             unsigned flags, const Plan& p, char* ws, hipStream_t s) {
+             unsigned flags, const Plan& p, char* ws, hipStream_t s,
+             const NormCtx<T>* norm = nullptr) {
     constexpr bool BF16 = (sizeof(T) == 2);
     const bool want_dx = !(flags & FLCE_SKIP_DX), want_dw = !(flags & FLCE_SKIP_DW);
     float* row_loss = reinterpret_cast<float*>(ws + p.off_row_loss);
@@ -219,6 +235,13 @@ int run_head(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t
         const int64_t rows = (BT - r0 < p.C) ? BT - r0 : p.C;
         const bool last = (c == p.nchunks - 1);
         const T* Xc = X + r0 * H;
+        if (norm) {   // X holds the raw hidden states: normalise this chunk
+            ScopedKernelTimer timer(FLCE_KIND_OTHER, s);
+            hipLaunchKernelGGL((rmsnorm_fwd_kernel<T>), dim3((unsigned)rows), dim3(RN_THREADS), 0, s,
+                               X + r0 * H, norm->gamma, norm->eps, (int)H, norm->Y, norm->rstd);
+            HIP_TRY(hipGetLastError());
+            Xc = norm->Y;
+        }
 
         // logits of the chunk: Z = X_c W^T
         if (BF16 && p.fast_logits) {
@@ -235,7 +258,7 @@ int run_head(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t
 
         // dX_c (+)= G W
         if (want_dx) {
-            T* dXc = dX + r0 * H;
+            T* dXc = norm ? norm->dY : dX + r0 * H;
             if (BF16 && p.fast_dx) {
                 if constexpr (BF16) {
                     if (p.dx_ksplit > 1) {
@@ -263,6 +286,13 @@ int run_head(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t
             } else {
                 FLCE_TRY((launch_gemm_generic<T, T>(FLCE_KIND_DX_GEMM, Z, p.ldz, WT, p.ldz, dXc, H, rows,
                                                     H, V, dx_add, s)));
+            }
+            if (norm) {
+                ScopedKernelTimer timer(FLCE_KIND_OTHER, s);
+                hipLaunchKernelGGL((rmsnorm_bwd_kernel<T>), dim3(RN_SLOTS), dim3(RN_THREADS), 0, s,
+                                   X + r0 * H, norm->gamma, norm->rstd, norm->dY, (int)rows, (int)H,
+                                   norm->dh + r0 * H, norm->partial);
+                HIP_TRY(hipGetLastError());
             }
         }
 
@@ -338,6 +368,55 @@ int check_dims(int64_t BT, int64_t H, int64_t V, int dtype) {
     return FLCE_OK;
 }
 
+struct NormLayout {
+    size_t off_y, off_dy, off_rstd, off_partial, total;
+};
+NormLayout norm_layout(const Plan& p, int64_t H, int dtype) {
+    NormLayout l{};
+    size_t off = p.total;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off += (bytes + 255) / 256 * 256;
+        return at;
+    };
+    l.off_y = take((size_t)p.C * H * elem_size(dtype));
+    l.off_dy = take((size_t)p.C * H * elem_size(dtype));
+    l.off_rstd = take((size_t)p.C * sizeof(float));
+    l.off_partial = take((size_t)RN_SLOTS * H * sizeof(float));
+    l.total = off;
+    return l;
+}
+
+template <typename T>
+int run_rmsnorm_head(const T* h, const T* gamma, float eps, const T* W, const int64_t* targets,
+                     int64_t BT, int64_t H, int64_t V, int64_t ignore_index, float* loss, T* dh,
+                     T* dgamma, T* dW, unsigned flags, const Plan& p, const NormLayout& l, char* ws,
+                     hipStream_t s) {
+    const bool want_dx = !(flags & FLCE_SKIP_DX);
+    NormCtx<T> n{gamma, eps, reinterpret_cast<T*>(ws + l.off_y), reinterpret_cast<T*>(ws + l.off_dy),
+                 reinterpret_cast<float*>(ws + l.off_rstd), reinterpret_cast<float*>(ws + l.off_partial),
+                 dh};
+    DeviceHeader* hdr = reinterpret_cast<DeviceHeader*>(ws + p.off_hdr);
+    if (want_dx) {
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(256), dim3(256), 0, s, n.partial,
+                           (int64_t)RN_SLOTS * H);
+        HIP_TRY(hipGetLastError());
+    }
+    FLCE_TRY(run_head<T>(h, W, targets, BT, H, V, ignore_index, 1.0f, hdr, false, nullptr, dW, flags, p,
+                         ws, s, &n));
+    if (want_dx) {
+        hipLaunchKernelGGL((rmsnorm_dgamma_kernel<T>), dim3((unsigned)((H + 255) / 256)), dim3(256), 0,
+                           s, n.partial, (int)H, dgamma);
+        HIP_TRY(hipGetLastError());
+    }
+    HeadWeights one{};
+    one.w[0] = 1.0f;
+    hipLaunchKernelGGL(finalize_loss_kernel, dim3(1), dim3(64), 0, s, hdr, 1, one, loss,
+                       static_cast<float*>(nullptr));
+    HIP_TRY(hipGetLastError());
+    return FLCE_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -376,6 +455,45 @@ int flce_multihead_fwd_bwd(const void* X, const void* const* W, const int64_t* c
     return run_heads<bf16_t>(static_cast<const bf16_t*>(X), W, targets, weights, n_heads, BT, H, V,
                              ignore_index, loss, head_losses, static_cast<bf16_t*>(dX), dW, flags, p,
                              ws, s);
+}
+
+int flce_rmsnorm_fwd_bwd(const void* h, const void* gamma, float eps, const void* W,
+                         const int64_t* targets, int64_t BT, int64_t H, int64_t V,
+                         int64_t ignore_index, int dtype, float* loss, void* dh, void* dgamma,
+                         void* dW, unsigned flags, void* stream) {
+    FLCE_TRY(check_dims(BT, H, V, dtype));
+    if (flags & ~(unsigned)(FLCE_SKIP_DX | FLCE_SKIP_DW)) return FLCE_ERR_ARG;
+    const bool want_dx = !(flags & FLCE_SKIP_DX), want_dw = !(flags & FLCE_SKIP_DW);
+    if (!h || !gamma || !W || !targets || !loss || (want_dx && (!dh || !dgamma)) || (want_dw && !dW))
+        return FLCE_ERR_NULL;
+    if (!aligned(h, 16) || !aligned(W, 16) || !aligned(gamma, elem_size(dtype)) ||
+        (want_dx && (!aligned(dh, 16) || !aligned(dgamma, elem_size(dtype)))) ||
+        (want_dw && !aligned(dW, 16)) || !aligned(targets, 8) || !aligned(loss, 4))
+        return FLCE_ERR_ALIGN;
+    if (ignore_index >= 0 && ignore_index < V) return FLCE_ERR_ARG;
+    if (!(eps >= 0.0f) || eps - eps != 0.0f) return FLCE_ERR_ARG;   // negative, NaN or infinite
+
+    const Plan p = make_plan(BT, H, V, dtype, g_budget);
+    const NormLayout l = norm_layout(p, H, dtype);
+    char* ws = nullptr;
+    FLCE_TRY(acquire_workspace(l.total, &ws));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dtype == FLCE_F32)
+        return run_rmsnorm_head<float>(static_cast<const float*>(h), static_cast<const float*>(gamma),
+                                       eps, static_cast<const float*>(W), targets, BT, H, V,
+                                       ignore_index, loss, static_cast<float*>(dh),
+                                       static_cast<float*>(dgamma), static_cast<float*>(dW), flags, p,
+                                       l, ws, s);
+    return run_rmsnorm_head<bf16_t>(static_cast<const bf16_t*>(h), static_cast<const bf16_t*>(gamma),
+                                    eps, static_cast<const bf16_t*>(W), targets, BT, H, V,
+                                    ignore_index, loss, static_cast<bf16_t*>(dh),
+                                    static_cast<bf16_t*>(dgamma), static_cast<bf16_t*>(dW), flags, p,
+                                    l, ws, s);
+}
+
+size_t flce_rmsnorm_workspace_bytes(int64_t BT, int64_t H, int64_t V, int dtype) {
+    if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
+    return norm_layout(make_plan(BT, H, V, dtype, g_budget), H, dtype).total;
 }
 
 int flce_fwd_bwd_ex(const void* X, const void* W, const int64_t* targets, int64_t BT, int64_t H,

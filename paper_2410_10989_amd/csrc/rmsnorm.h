@@ -1,0 +1,94 @@
+// RMSNorm in front of the output projection (paper section 3.2, RMSNorm
+// paragraph, Eq. RMSNorm-forward / RMSNorm-backward), row by row:
+//
+//     rms = sqrt(sum_j x_j^2 / n + eps),  xhat = x / rms,  y = xhat * gamma
+//     dx     = (1/rms) * (dy*gamma - [xhat . (dy*gamma) / n] * xhat)
+//     dgamma = sum over rows of dy * xhat
+//
+// All arithmetic in fp32 on values widened from the storage type; y and dx are
+// rounded once when stored.  dgamma is summed without atomics: the backward
+// kernel runs RN_SLOTS workgroups, workgroup p owns rows p, p + RN_SLOTS, ... and
+// row p of an fp32 partial buffer [RN_SLOTS x n]; a second kernel adds the
+// partial rows in fixed order.  The kernels are bandwidth bound and touch
+// O(rows * n) bytes, which is negligible next to the three products.
+#pragma once
+#include "flce_device.h"
+
+namespace flce {
+
+constexpr int RN_THREADS = 256;
+constexpr int RN_SLOTS = 256;
+
+// Sum over the 256 threads of a workgroup, the same value returned to every thread.
+__device__ __forceinline__ float rn_block_sum(float v, float* red) {
+    v = wave_sum(v);
+    __syncthreads();   // red may still be read from a previous call
+    if ((threadIdx.x & (WAVE - 1)) == 0) red[threadIdx.x / WAVE] = v;
+    __syncthreads();
+    return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// One workgroup per row: y = x / rms(x) * gamma, rstd[row] = 1 / rms(x).
+template <typename T>
+__global__ __launch_bounds__(RN_THREADS) void rmsnorm_fwd_kernel(const T* __restrict__ x,
+                                                                 const T* __restrict__ gamma,
+                                                                 float eps, int n,
+                                                                 T* __restrict__ y,
+                                                                 float* __restrict__ rstd) {
+    __shared__ float red[RN_THREADS / WAVE];
+    const int64_t base = (int64_t)blockIdx.x * n;
+    float ss = 0.f;
+    for (int j = threadIdx.x; j < n; j += RN_THREADS) {
+        const float v = to_f32(x[base + j]);
+        ss += v * v;
+    }
+    ss = rn_block_sum(ss, red);
+    const float r = 1.0f / sqrtf(ss / (float)n + eps);
+    if (threadIdx.x == 0) rstd[blockIdx.x] = r;
+    for (int j = threadIdx.x; j < n; j += RN_THREADS)
+        y[base + j] = from_f32<T>(to_f32(x[base + j]) * r * to_f32(gamma[j]));
+}
+
+// Workgroup p: rows p, p + RN_SLOTS, ... of this chunk.  dx is written; the
+// workgroup's own row of `partial` accumulates dy * xhat (column j always by the
+// same thread, so there is no race and the order of additions is fixed).
+template <typename T>
+__global__ __launch_bounds__(RN_THREADS) void rmsnorm_bwd_kernel(
+    const T* __restrict__ x, const T* __restrict__ gamma, const float* __restrict__ rstd,
+    const T* __restrict__ dy, int rows, int n, T* __restrict__ dx, float* __restrict__ partial) {
+    __shared__ float red[RN_THREADS / WAVE];
+    float* mine = partial + (int64_t)blockIdx.x * n;
+    for (int row = blockIdx.x; row < rows; row += RN_SLOTS) {
+        const int64_t base = (int64_t)row * n;
+        const float r = rstd[row];
+        float dot = 0.f;
+        for (int j = threadIdx.x; j < n; j += RN_THREADS)
+            dot += (to_f32(x[base + j]) * r) * (to_f32(dy[base + j]) * to_f32(gamma[j]));
+        dot = rn_block_sum(dot, red) / (float)n;
+        for (int j = threadIdx.x; j < n; j += RN_THREADS) {
+            const float xh = to_f32(x[base + j]) * r;
+            const float d = to_f32(dy[base + j]);
+            dx[base + j] = from_f32<T>(r * (d * to_f32(gamma[j]) - dot * xh));
+            mine[j] += d * xh;
+        }
+    }
+}
+
+__global__ void fill_zero_kernel(float* __restrict__ p, int64_t count) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+         i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = 0.f;
+}
+
+// dgamma[j] = sum_p partial[p][j], p = 0, 1, ... in order.
+template <typename T>
+__global__ void rmsnorm_dgamma_kernel(const float* __restrict__ partial, int n,
+                                      T* __restrict__ dgamma) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= n) return;
+    float s = 0.f;
+    for (int p = 0; p < RN_SLOTS; ++p) s += partial[(int64_t)p * n + j];
+    dgamma[j] = from_f32<T>(s);
+}
+
+}  // namespace flce

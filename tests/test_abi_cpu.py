@@ -101,6 +101,17 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert heads(wts=F2(1.0, float("nan"))) == 7 and heads(wts=F2(float("inf"), 1.0)) == 7
     assert heads(W=P2(a + 256, a + 1538)) == 4
     assert heads(flags=8) == 7
+    # RMSNorm in front of the projection
+    cf = ctypes.c_float
+
+    def norm(h=a, gamma=a + 2048, eps=1e-6, dh=a + 1024, dg=a + 2304, dW=a + 1280, flags=0):
+        return L.flce_rmsnorm_fwd_bwd(h, gamma, cf(eps), a + 256, a + 512, 4, 8, 16, -100, 1, a + 768,
+                                      dh, dg, dW, flags, None)
+
+    assert norm(gamma=None) == 1 and norm(dg=None) == 1 and norm(dh=None) == 1
+    assert norm(gamma=a + 2049) == 4 and norm(h=a + 4) == 4
+    assert norm(eps=-1.0) == 7 and norm(eps=float("nan")) == 7 and norm(eps=float("inf")) == 7
+    assert norm(flags=4) == 7
     assert L.flce_set_logits_budget_bytes(0) == 7
     assert L.flce_cross_entropy_inplace(None, a, 1, 1, 1, -100, 1, a, None) == 1
     assert L.flce_cross_entropy_inplace(a, a, 4, 16, 8, -100, 1, a, None) == 2   # ldz < V

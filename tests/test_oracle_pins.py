@@ -297,3 +297,83 @@ def test_multihead_workload_shifts_targets_inside_sequences():
             assert np.array_equal(tj[s:e - j], t0[s + j:e])
     assert m.weights == [1.0, 0.8, 0.8 ** 2]
     assert not np.array_equal(m.Ws[1], m.Ws[2]) and m.Ws[0] is m.base.W
+
+
+# ---- RMSNorm in front of the projection (paper section 3.2, RMSNorm paragraph) ----
+
+def _norm_case(BT=9, H=6, V=7, seed=21):
+    g = np.random.default_rng(seed)
+    h = g.standard_normal((BT, H)) * 1.7
+    gamma = 1.0 + 0.3 * g.standard_normal(H)
+    W = g.standard_normal((V, H)) * 0.5
+    t = g.integers(0, V, size=BT).astype(np.int64)
+    t[4] = IGN
+    return h, gamma, W, t
+
+
+@pytest.mark.parametrize("eps", [1e-6, 0.5])
+def test_rmsnorm_flce_matches_autograd_of_the_composed_definition(eps):
+    # A large eps makes a wrong place of eps (outside the root, inside the mean) visible.
+    h, gamma, W, t = _norm_case()
+    r = oracle.rmsnorm_flce(h, gamma, eps, W, t, IGN)
+    ht = torch.tensor(h, requires_grad=True)
+    gt = torch.tensor(gamma, requires_grad=True)
+    Wt = torch.tensor(W, requires_grad=True)
+    y = ht * torch.rsqrt(ht.pow(2).mean(dim=1, keepdim=True) + eps) * gt
+    loss = torch.nn.functional.cross_entropy(y @ Wt.T, torch.tensor(t), ignore_index=IGN)
+    loss.backward()
+    assert abs(r.loss - loss.item()) <= 1e-13 * abs(loss.item())
+    np.testing.assert_allclose(r.y, y.detach().numpy(), rtol=0, atol=1e-14)
+    np.testing.assert_allclose(r.dh, ht.grad.numpy(), rtol=0, atol=1e-14)
+    np.testing.assert_allclose(r.dgamma, gt.grad.numpy(), rtol=0, atol=1e-14)
+    np.testing.assert_allclose(r.dW, Wt.grad.numpy(), rtol=0, atol=1e-14)
+    assert np.abs(r.dh).max() > 1e-3 and np.abs(r.dgamma).max() > 1e-3
+
+
+def test_rmsnorm_gradients_match_finite_differences_of_the_loss():
+    h, gamma, W, t = _norm_case(BT=5, H=4, V=5)
+    eps, d = 1e-3, 1e-6
+    r = oracle.rmsnorm_flce(h, gamma, eps, W, t, IGN)
+
+    def loss_at(hp, gp):
+        return oracle.rmsnorm_flce(hp, gp, eps, W, t, IGN, want_dh=False, want_dW=False).loss
+
+    fd_h = np.zeros_like(h)
+    for idx in np.ndindex(*h.shape):
+        hp, hm = h.copy(), h.copy()
+        hp[idx] += d
+        hm[idx] -= d
+        fd_h[idx] = (loss_at(hp, gamma) - loss_at(hm, gamma)) / (2 * d)
+    fd_g = np.zeros_like(gamma)
+    for j in range(gamma.size):
+        gp, gm = gamma.copy(), gamma.copy()
+        gp[j] += d
+        gm[j] -= d
+        fd_g[j] = (loss_at(h, gp) - loss_at(h, gm)) / (2 * d)
+    assert np.abs(fd_h - r.dh).max() <= 1e-8 * max(1.0, np.abs(r.dh).max())
+    assert np.abs(fd_g - r.dgamma).max() <= 1e-8 * max(1.0, np.abs(r.dgamma).max())
+
+
+def test_rmsnorm_without_eps_is_scale_invariant_and_dh_is_orthogonal_to_h():
+    # eps = 0: y does not change when a row of h is scaled, so the loss cannot change
+    # along h: every row of dh is orthogonal to its row of h, and dh scales with 1/a.
+    h, gamma, W, t = _norm_case()
+    r1 = oracle.rmsnorm_flce(h, gamma, 0.0, W, t, IGN)
+    r3 = oracle.rmsnorm_flce(3.0 * h, gamma, 0.0, W, t, IGN)
+    assert abs(r1.loss - r3.loss) <= 1e-14
+    np.testing.assert_allclose(r3.dh, r1.dh / 3.0, rtol=0, atol=1e-15)
+    np.testing.assert_allclose(r3.dgamma, r1.dgamma, rtol=0, atol=1e-14)
+    assert np.abs((r1.dh * h).sum(axis=1)).max() <= 1e-15
+    # rows of y have mean square gamma-weighted 1: with gamma = 1, |y_i|^2 = n
+    r = oracle.rmsnorm_flce(h, np.ones_like(gamma), 0.0, W, t, IGN, want_dh=False, want_dW=False)
+    np.testing.assert_allclose((r.y ** 2).sum(axis=1), h.shape[1], rtol=1e-14)
+
+
+def test_rmsnorm_of_unit_rms_rows_with_unit_gamma_is_the_plain_path():
+    h, gamma, W, t = _norm_case()
+    h = h / np.sqrt((h * h).mean(axis=1, keepdims=True))      # every row has RMS 1
+    r = oracle.rmsnorm_flce(h, np.ones_like(gamma), 0.0, W, t, IGN)
+    r0 = oracle.flce(h, W, t, IGN)
+    assert abs(r.loss - r0.loss) <= 1e-14
+    np.testing.assert_allclose(r.dW, r0.dW, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(r.dgamma, (r0.dX * h).sum(axis=0), rtol=0, atol=1e-14)
