@@ -35,14 +35,16 @@ struct Plan {
 };
 
 // How many K ranges to cut a product with `tiles` output tiles and `ksteps` K steps
-// into, so that tiles * ranges fills whole rounds of the chip's 256 CUs.  Prefers
-// few ranges (each costs an fp32 partial result) and keeps ranges long.
-inline int choose_ksplit(int64_t tiles, int64_t ksteps) {
+// into, so that tiles * ranges fills whole rounds of the chip's 256 CUs (one tile per
+// CU at a time).  288 tiles, for example, run as two rounds at 56 % occupancy; cut
+// into 8 ranges they are 9 full rounds.  Prefers few ranges (each costs an fp32
+// partial result) and keeps ranges long; with many rounds the tail does not matter
+// and the answer is 1.
+inline int choose_ksplit(int64_t tiles, int64_t ksteps, int max_ranges) {
     constexpr int64_t CUS = 256, MIN_STEPS = 64;
-    if (tiles >= CUS) return 1;
     int best = 1;
     double best_eff = 0.0;
-    for (int s = 1; s <= 16 && ksteps / s >= MIN_STEPS; ++s) {
+    for (int s = 1; s <= 16 && s <= max_ranges && ksteps / s >= MIN_STEPS; ++s) {
         const int64_t work = tiles * s;
         const double eff = (double)work / (double)(((work + CUS - 1) / CUS) * CUS);
         if (eff > best_eff + 0.02) {
@@ -51,6 +53,14 @@ inline int choose_ksplit(int64_t tiles, int64_t ksteps) {
         }
     }
     return best;
+}
+
+// The fp32 partial results of a cut dX product (ranges x rows x H) may take as much
+// memory as the logits chunk, not more.
+inline int max_dx_ranges(size_t budget_bytes, int64_t rows, int64_t H) {
+    const size_t one = (size_t)rows * (size_t)H * sizeof(float);
+    const size_t n = one ? budget_bytes / one : 1;
+    return (int)std::max<size_t>(1, std::min<size_t>(n, 16));
 }
 
 // Limits of the tuned kernel's 32-bit offsets inside one tile (see gemm_bf16_nt.h).
@@ -97,7 +107,8 @@ inline Plan make_plan(int64_t BT, int64_t H, int64_t V, int dtype, size_t budget
     }
     if (p.fast_dx) {
         const int64_t rows = p.nchunks > 1 ? p.C : rows_last;
-        p.dx_ksplit = choose_ksplit(((rows + 255) / 256) * ((H + 255) / 256), V / 64);
+        p.dx_ksplit = choose_ksplit(((rows + 255) / 256) * ((H + 255) / 256), V / 64,
+                                    max_dx_ranges(budget_bytes, round_up(rows, 256), H));
     }
     const bool need_wt = !p.fast_dx;
     const bool need_gt = !(p.fast_dw_full && p.fast_dw_last);
@@ -119,7 +130,8 @@ inline Plan make_plan(int64_t BT, int64_t H, int64_t V, int dtype, size_t budget
     if (worst_case_bt && p.fast_dx) {
         // the bound has to hold for every chunk size the scheduler can pick
         for (int64_t c = CHUNK_ALIGN; c <= cmax; c += CHUNK_ALIGN) {
-            const int ks = choose_ksplit((c / 256) * ((H + 255) / 256), V / 64);
+            const int ks = choose_ksplit((c / 256) * ((H + 255) / 256), V / 64,
+                                         max_dx_ranges(budget_bytes, c, H));
             if (ks > 1) dxpart = std::max(dxpart, (size_t)ks * c * H * sizeof(float));
         }
     }

@@ -51,6 +51,12 @@ def test_ragged_shapes(dtype, BT, H, V, ignore):
     check_full(workloads.make(BT, H, V, dtype, ignore=ignore, seed=1000 + BT + V, name="ragged"))
 
 
+def test_dx_is_cut_along_k_when_the_tile_count_leaves_a_poor_last_round():
+    # 17 x 16 = 272 output tiles of dX on 256 CUs would run as two rounds; the scheduler
+    # cuts K = V in two ranges instead (fp32 partials, fixed-order sum)
+    check_full(workloads.make(4352, 4096, 8192, "bf16", ignore=("iid", 0.1), seed=272, name="tail"))
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_several_chunks_with_ragged_last_chunk(dtype):
     # A budget of 256 rows of logits forces 3 chunks (256, 256, 1 rows); the
