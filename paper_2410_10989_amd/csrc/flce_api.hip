@@ -161,10 +161,10 @@ int launch_ce_rows(T* Z, int64_t ldz, const int64_t* targets, int64_t rows, int6
                    int64_t ignore_index, DeviceHeader* hdr, float* row_loss, hipStream_t s) {
     const bool vec = aligned(Z, 16) && ((ldz * sizeof(T)) % 16 == 0);
     ScopedKernelTimer timer(FLCE_KIND_CE_ROWS, s);
-    // rows of 128 KB up to what the register cache holds (256 KB): measured 6-12 % faster
-    // than two sweeps there, slower for shorter and for longer rows
-    if (vec && V * (int64_t)sizeof(T) >= 131072 &&
-        V * (int64_t)sizeof(T) <= (int64_t)RC_THREADS * RC_NV * 16)
+    // rows from 96 KB on: the 1024-thread kernel that keeps the first 256 KB of the row in
+    // registers (measured 4.6-5.3 TB/s against 3.4-3.9 for two plain sweeps; below 96 KB
+    // the 256-thread kernel's higher occupancy wins)
+    if (vec && V * (int64_t)sizeof(T) >= 98304)
         hipLaunchKernelGGL((ce_rows_cached_kernel<T>), dim3((unsigned)rows), dim3(RC_THREADS), 0, s, Z,
                            ldz, targets, (int)V, ignore_index, hdr, row_loss);
     else if (vec)

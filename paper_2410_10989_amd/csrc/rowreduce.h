@@ -14,7 +14,7 @@ namespace flce {
 constexpr int RR_THREADS = 256;
 
 struct MaxSum {
-    float m, s;
+    float m, s;   // running maximum and sum of exp(z - m)
 };
 __device__ __forceinline__ MaxSum ms_merge(MaxSum a, MaxSum b) {
     const float m = fmaxf(a.m, b.m);
@@ -24,97 +24,192 @@ __device__ __forceinline__ MaxSum ms_merge(MaxSum a, MaxSum b) {
     const float sb = (b.m == -INFINITY) ? 0.f : b.s * __expf(b.m - m);
     return {m, sa + sb};
 }
-__device__ __forceinline__ void ms_push(MaxSum& a, float x) {
-    if (x > a.m) {
-        a.s = a.s * __expf(a.m - x) + 1.f;   // a.m = -inf gives 0 * 0 + 1
-        a.m = x;
-    } else {
-        a.s += __expf(x - a.m);
+
+// The arithmetic per logit decides the speed of these kernels as much as the memory
+// traffic does (a CU retires 64 plain and 16 transcendental lane operations per
+// cycle), so both sweeps work on whole 16-byte vectors and exponentials are taken as
+// exp2(fma(z, log2 e, c)): one multiply-add and one v_exp_f32 per logit.
+constexpr float RR_LOG2E = 1.4426950408889634f;
+
+template <typename T> struct RowVec;
+template <> struct RowVec<float> {
+    static constexpr int N = 4;
+    static __device__ __forceinline__ void unpack(const u32x4& raw, float (&f)[4]) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) f[w] = __uint_as_float(raw[w]);
     }
+    static __device__ __forceinline__ u32x4 pack(const float (&f)[4]) {
+        u32x4 r;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) r[w] = __float_as_uint(f[w]);
+        return r;
+    }
+};
+template <> struct RowVec<bf16_t> {
+    static constexpr int N = 8;
+    // a bf16 is the upper half of the float with the same value
+    static __device__ __forceinline__ void unpack(const u32x4& raw, float (&f)[8]) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            f[2 * w] = __uint_as_float(raw[w] << 16);
+            f[2 * w + 1] = __uint_as_float(raw[w] & 0xffff0000u);
+        }
+    }
+    static __device__ __forceinline__ u32x4 pack(const float (&f)[8]) {
+        u32x4 r;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const bf16x2 p = {(bf16_t)f[2 * w], (bf16_t)f[2 * w + 1]};   // round to nearest even
+            r[w] = __builtin_bit_cast(uint32_t, p);
+        }
+        return r;
+    }
+};
+
+// exp(z - ref).  bf16 logits: exp2(fma(z, log2 e, -ref log2 e)), the rounding of the
+// constant (half an ulp of |ref| log2 e) is far below what bf16 resolves.  fp32
+// logits: the difference is taken first, which stays exact for large |z|.
+template <typename T> struct RowExp;
+template <> struct RowExp<bf16_t> {
+    float c;
+    __device__ __forceinline__ explicit RowExp(float ref) : c(-ref * RR_LOG2E) {}
+    __device__ __forceinline__ float operator()(float z) const {
+        return __builtin_amdgcn_exp2f(fmaf(z, RR_LOG2E, c));
+    }
+};
+template <> struct RowExp<float> {
+    float ref;
+    __device__ __forceinline__ explicit RowExp(float r) : ref(r) {}
+    __device__ __forceinline__ float operator()(float z) const {
+        return __builtin_amdgcn_exp2f((z - ref) * RR_LOG2E);
+    }
+};
+
+// Online softmax update with N logits at once: one rescale of the running sum per
+// vector instead of one decision per logit.
+template <typename T, int N>
+__device__ __forceinline__ void ms_push_vec(MaxSum& a, const float (&f)[N]) {
+    float vm = f[0];
+#pragma unroll
+    for (int j = 1; j < N; ++j) vm = fmaxf(vm, f[j]);
+    const float m_new = fmaxf(a.m, vm);
+    // a row may start with -inf logits: keep the reference finite
+    const RowExp<T> ex((m_new == -INFINITY) ? 0.f : m_new);
+    float s = a.s * ex(a.m);   // a.m = -inf: s was 0 and stays 0
+#pragma unroll
+    for (int j = 0; j < N; ++j) s += ex(f[j]);
+    a.m = m_new;
+    a.s = s;
+}
+template <typename T>
+__device__ __forceinline__ void ms_push(MaxSum& a, float x) {
+    const float f[1] = {x};
+    ms_push_vec<T, 1>(a, f);
+}
+
+// (softmax - onehot) / N of one vector: exp(z - lse) * inv_n; the one-hot term only
+// touches the vector that holds the target column.
+template <typename T>
+__device__ __forceinline__ u32x4 ce_gradient_vec(const u32x4& raw, int i, int tcol,
+                                                 const RowExp<T>& ex, float inv_n) {
+    constexpr int N = RowVec<T>::N;
+    float f[N];
+    RowVec<T>::unpack(raw, f);
+#pragma unroll
+    for (int j = 0; j < N; ++j) f[j] = ex(f[j]) * inv_n;
+    if (i == tcol / N) {
+#pragma unroll
+        for (int j = 0; j < N; ++j)
+            if (j == tcol % N) f[j] -= inv_n;
+    }
+    return RowVec<T>::pack(f);
+}
+template <typename T>
+__device__ __forceinline__ T ce_gradient_one(T z, int v, int tcol, const RowExp<T>& ex, float inv_n) {
+    float g = ex(to_f32(z)) * inv_n;
+    if (v == tcol) g -= inv_n;
+    return from_f32<T>(g);
+}
+
+// Merges the per-thread pairs of a workgroup of NW wavefronts; thread 0 then holds
+// the row's log-sum-exp, publishes it and the row's loss.  Ends with a barrier, so
+// z[target] has been read before any thread overwrites the row.
+template <typename T, int NW>
+__device__ __forceinline__ float row_lse(MaxSum a, const T* z, int64_t t, int row,
+                                         float* __restrict__ row_loss, MaxSum* part, float* s_lse) {
+    const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE;
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) {
+        MaxSum b = {__shfl_xor(a.m, o, WAVE), __shfl_xor(a.s, o, WAVE)};
+        a = ms_merge(a, b);
+    }
+    if (lane == 0) part[wave] = a;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        MaxSum r = part[0];
+        for (int w = 1; w < NW; ++w) r = ms_merge(r, part[w]);
+        const float l = r.m + logf(r.s);
+        *s_lse = l;
+        row_loss[row] = l - to_f32(z[t]);
+    }
+    __syncthreads();
+    return *s_lse;
 }
 
 template <typename T, bool VEC16>
 __global__ __launch_bounds__(RR_THREADS) void ce_rows_inplace_kernel(
     T* __restrict__ Z, int64_t ldz, const int64_t* __restrict__ targets, int V,
     int64_t ignore_index, const DeviceHeader* __restrict__ hdr, float* __restrict__ row_loss) {
-    constexpr int VEC = 16 / sizeof(T);
+    constexpr int VEC = RowVec<T>::N;
     const int row = blockIdx.x;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x;
     T* z = Z + (int64_t)row * ldz;
     const int64_t t = targets[row];
     const bool valid = (t != ignore_index);
+    u32x4* zv = reinterpret_cast<u32x4*>(z);
 
     __shared__ MaxSum part[RR_THREADS / WAVE];
     __shared__ float s_lse;
 
     const int nvec = VEC16 ? V / VEC : 0;
-    float lse = 0.f;
-    if (valid) {
-        MaxSum a = {-INFINITY, 0.f};
-        if constexpr (VEC16) {
-            for (int i = tid; i < nvec; i += RR_THREADS) {
-                u32x4 raw = reinterpret_cast<const u32x4*>(z)[i];
-                const T* e = reinterpret_cast<const T*>(&raw);
-#pragma unroll
-                for (int j = 0; j < VEC; ++j) ms_push(a, to_f32(e[j]));
-            }
-        }
-        for (int v = nvec * VEC + tid; v < V; v += RR_THREADS) ms_push(a, to_f32(z[v]));
-#pragma unroll
-        for (int o = WAVE / 2; o > 0; o >>= 1) {
-            MaxSum b = {__shfl_xor(a.m, o, WAVE), __shfl_xor(a.s, o, WAVE)};
-            a = ms_merge(a, b);
-        }
-        if (lane == 0) part[wave] = a;
-        __syncthreads();
-        if (tid == 0) {
-            MaxSum r = part[0];
-            for (int w = 1; w < RR_THREADS / WAVE; ++w) r = ms_merge(r, part[w]);
-            const float l = r.m + logf(r.s);
-            s_lse = l;
-            row_loss[row] = l - to_f32(z[t]);
-        }
-        __syncthreads();   // z[target] is read before anybody overwrites the row
-        lse = s_lse;
-    } else if (tid == 0) {
-        row_loss[row] = 0.f;
+    if (!valid) {   // uniform per workgroup
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        for (int i = tid; i < nvec; i += RR_THREADS) zv[i] = zero;
+        for (int v = nvec * VEC + tid; v < V; v += RR_THREADS) z[v] = from_f32<T>(0.f);
+        if (tid == 0) row_loss[row] = 0.f;
+        return;
     }
 
-    const float inv_n = hdr->inv_n;
-    const int tcol = valid ? (int)t : -1;
+    MaxSum a = {-INFINITY, 0.f};
     if constexpr (VEC16) {
         for (int i = tid; i < nvec; i += RR_THREADS) {
-            u32x4 raw = {0u, 0u, 0u, 0u};
-            if (valid) {
-                raw = reinterpret_cast<const u32x4*>(z)[i];
-                T* e = reinterpret_cast<T*>(&raw);
-#pragma unroll
-                for (int j = 0; j < VEC; ++j) {
-                    float g = __expf(to_f32(e[j]) - lse) * inv_n;
-                    if (i * VEC + j == tcol) g -= inv_n;
-                    e[j] = from_f32<T>(g);
-                }
-            }
-            reinterpret_cast<u32x4*>(z)[i] = raw;
+            float f[VEC];
+            RowVec<T>::unpack(zv[i], f);
+            ms_push_vec<T, VEC>(a, f);
         }
     }
-    for (int v = nvec * VEC + tid; v < V; v += RR_THREADS) {
-        float g = 0.f;
-        if (valid) {
-            g = __expf(to_f32(z[v]) - lse) * inv_n;
-            if (v == tcol) g -= inv_n;
-        }
-        z[v] = from_f32<T>(g);
+    for (int v = nvec * VEC + tid; v < V; v += RR_THREADS) ms_push<T>(a, to_f32(z[v]));
+    const float lse = row_lse<T, RR_THREADS / WAVE>(a, z, t, row, row_loss, part, &s_lse);
+
+    const float inv_n = hdr->inv_n;
+    const RowExp<T> ex(lse);
+    const int tcol = (int)t;
+    if constexpr (VEC16) {
+        for (int i = tid; i < nvec; i += RR_THREADS)
+            zv[i] = ce_gradient_vec<T>(zv[i], i, tcol, ex, inv_n);
     }
+    for (int v = nvec * VEC + tid; v < V; v += RR_THREADS)
+        z[v] = ce_gradient_one<T>(z[v], v, tcol, ex, inv_n);
 }
 
 // Variant for long rows: one workgroup of 1024 threads per row keeps the first
-// 1024 * RC_NV 16-byte vectors of the row (128 K bf16 logits) in registers between
-// the two sweeps, so that part of the row is read from HBM once instead of twice;
-// what is beyond is swept twice as above.  All of a thread's loads are issued
-// before the first is consumed.  16 wavefronts per CU keep the per-thread ALU phases
-// short (a variant with 4 wavefronts per CU and the whole row cached was slower
-// than two sweeps).  Used for rows of 128-256 KB, where it measures 6-12 % faster.
+// 1024 * RC_NV 16-byte vectors of the row (256 KB) in registers between the two
+// sweeps, so that part of the row is read from HBM once instead of twice; what is
+// beyond is swept twice as above.  All of a thread's loads are issued before the
+// first is consumed.  16 wavefronts per CU keep the per-thread ALU phases short (a
+// variant with 4 wavefronts per CU and the whole row cached was slower than two
+// sweeps).  Measured on rows of 96 KB and more: 4.6-5.3 TB/s of algorithmic traffic
+// against 3.4-3.9 TB/s for the two-sweep kernel; shorter rows are faster there.
 constexpr int RC_THREADS = 1024;
 constexpr int RC_NV = 16;
 
@@ -122,9 +217,9 @@ template <typename T>
 __global__ __launch_bounds__(RC_THREADS) void ce_rows_cached_kernel(
     T* __restrict__ Z, int64_t ldz, const int64_t* __restrict__ targets, int V,
     int64_t ignore_index, const DeviceHeader* __restrict__ hdr, float* __restrict__ row_loss) {
-    constexpr int VEC = 16 / sizeof(T);
+    constexpr int VEC = RowVec<T>::N;
     const int row = blockIdx.x;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x;
     T* z = Z + (int64_t)row * ldz;
     const int64_t t = targets[row];
     const bool valid = (t != ignore_index);
@@ -153,57 +248,37 @@ __global__ __launch_bounds__(RC_THREADS) void ce_rows_cached_kernel(
     for (int k = 0; k < RC_NV; ++k) {
         const int i = tid + k * RC_THREADS;
         if (i < nvec) {
-            const T* e = reinterpret_cast<const T*>(&keep[k]);
-#pragma unroll
-            for (int j = 0; j < VEC; ++j) ms_push(a, to_f32(e[j]));
+            float f[VEC];
+            RowVec<T>::unpack(keep[k], f);
+            ms_push_vec<T, VEC>(a, f);
         }
+        // one vector at a time: interleaving several would spill the cached row
+        __builtin_amdgcn_sched_barrier(0);
     }
     for (int i = tid + RC_NV * RC_THREADS; i < nvec; i += RC_THREADS) {   // beyond the cache
-        u32x4 raw = zv[i];
-        const T* e = reinterpret_cast<const T*>(&raw);
-#pragma unroll
-        for (int j = 0; j < VEC; ++j) ms_push(a, to_f32(e[j]));
+        float f[VEC];
+        RowVec<T>::unpack(zv[i], f);
+        ms_push_vec<T, VEC>(a, f);
     }
-    for (int v = nvec * VEC + tid; v < V; v += RC_THREADS) ms_push(a, to_f32(z[v]));
-#pragma unroll
-    for (int o = WAVE / 2; o > 0; o >>= 1) {
-        MaxSum b = {__shfl_xor(a.m, o, WAVE), __shfl_xor(a.s, o, WAVE)};
-        a = ms_merge(a, b);
-    }
-    if (lane == 0) part[wave] = a;
-    __syncthreads();
-    if (tid == 0) {
-        MaxSum r = part[0];
-        for (int w = 1; w < RC_THREADS / WAVE; ++w) r = ms_merge(r, part[w]);
-        const float l = r.m + logf(r.s);
-        s_lse = l;
-        row_loss[row] = l - to_f32(z[t]);
-    }
-    __syncthreads();   // z[target] is read before anybody overwrites the row
-    const float lse = s_lse;
+    for (int v = nvec * VEC + tid; v < V; v += RC_THREADS) ms_push<T>(a, to_f32(z[v]));
+    const float lse = row_lse<T, RC_THREADS / WAVE>(a, z, t, row, row_loss, part, &s_lse);
+
     const float inv_n = hdr->inv_n;
+    const RowExp<T> ex(lse);
     const int tcol = (int)t;
-    auto rewrite = [&](u32x4 raw, int i) {
-        T* e = reinterpret_cast<T*>(&raw);
-#pragma unroll
-        for (int j = 0; j < VEC; ++j) {
-            float g = __expf(to_f32(e[j]) - lse) * inv_n;
-            if (i * VEC + j == tcol) g -= inv_n;
-            e[j] = from_f32<T>(g);
-        }
-        zv[i] = raw;
-    };
 #pragma unroll
     for (int k = 0; k < RC_NV; ++k) {
         const int i = tid + k * RC_THREADS;
-        if (i < nvec) rewrite(keep[k], i);
+        // hide the value's history: otherwise the unpacked floats of sweep 1 are kept
+        // for reuse here, which does not fit the register file and spills
+        asm volatile("" : "+v"(keep[k]));
+        if (i < nvec) zv[i] = ce_gradient_vec<T>(keep[k], i, tcol, ex, inv_n);
+        __builtin_amdgcn_sched_barrier(0);
     }
-    for (int i = tid + RC_NV * RC_THREADS; i < nvec; i += RC_THREADS) rewrite(zv[i], i);
-    for (int v = nvec * VEC + tid; v < V; v += RC_THREADS) {
-        float g = __expf(to_f32(z[v]) - lse) * inv_n;
-        if (v == tcol) g -= inv_n;
-        z[v] = from_f32<T>(g);
-    }
+    for (int i = tid + RC_NV * RC_THREADS; i < nvec; i += RC_THREADS)
+        zv[i] = ce_gradient_vec<T>(zv[i], i, tcol, ex, inv_n);
+    for (int v = nvec * VEC + tid; v < V; v += RC_THREADS)
+        z[v] = ce_gradient_one<T>(z[v], v, tcol, ex, inv_n);
 }
 
 // Adds the per-row losses of one launch to the running sum, in a fixed order
