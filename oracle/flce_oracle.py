@@ -146,20 +146,21 @@ class RmsNormResult:
 
 
 def rmsnorm_flce(h, gamma, eps, W, targets, ignore_index=-100, want_dh=True,
-                 want_dW=True) -> RmsNormResult:
+                 want_dW=True, vocab=None) -> RmsNormResult:
     """RMSNorm (paper section 3.2, RMSNorm paragraph) followed by the projection
     and cross entropy.  Forward, row by row: RMS = sqrt(sum_j h_j^2 / n + eps),
     xhat = h / RMS, y = xhat * gamma.  Backward with g = dL/dy:
     dh = (g*gamma - [xhat . (g*gamma) / n] xhat) / RMS, dgamma = sum over rows of
-    g * xhat.  g is the dX of the linear cross-entropy oracle evaluated at X = y."""
+    g * xhat.  g is the dX of the linear cross-entropy oracle evaluated at X = y.
+    `vocab` restricts dW to those vocabulary ids."""
     h = np.asarray(h, dtype=np.float64)
     gamma = np.asarray(gamma, dtype=np.float64)
     n = h.shape[1]
     rms = np.sqrt((h * h).sum(axis=1) / n + eps)
     xhat = h / rms[:, None]
     y = xhat * gamma[None, :]
-    r = flce(y, np.asarray(W, dtype=np.float64), targets, ignore_index, want_dX=want_dh,
-             want_dW=want_dW)
+    r = flce(y, np.asarray(W, dtype=np.float64), targets, ignore_index, vocab=vocab,
+             want_dX=want_dh, want_dW=want_dW)
     dh = dgamma = None
     if want_dh:
         gg = r.dX * gamma[None, :]

@@ -133,7 +133,7 @@ int launch_gemm_fast(int kind, const bf16_t* A, int64_t lda, const bf16_t* B, in
                      int64_t ldc, const InT* Cin, int64_t ldcin, int64_t M, int64_t N, int64_t K,
                      hipStream_t s, int ksplit = 1, int64_t split_stride = 0) {
     if (M <= 0 || N <= 0 || K <= 0) return FLCE_OK;
-    if (K % FG_BK != 0 || !aligned(A, 16) || !aligned(B, 16)) return FLCE_ERR_ARG;
+    if (!aligned(A, 16) || !aligned(B, 16)) return FLCE_ERR_ARG;
     ScopedKernelTimer timer(kind, s);
     FGArgs a{A, lda, B, ldb, C, ldc, Cin, ldcin, (int)M, (int)N, (int)K,
              (int)((M + FG_BM - 1) / FG_BM), (int)((N + FG_BN - 1) / FG_BN), ksplit, split_stride};
@@ -156,9 +156,12 @@ int launch_transpose(const T* in, int64_t ldin, T* out, int64_t ldout, int64_t R
     return FLCE_OK;
 }
 
+// zero_pad: columns V .. V + zero_pad - 1 of every row are set to zero as well (the
+// padding of the workspace's dlogits chunk, which the dX product reads as part of K).
 template <typename T>
 int launch_ce_rows(T* Z, int64_t ldz, const int64_t* targets, int64_t rows, int64_t V,
-                   int64_t ignore_index, DeviceHeader* hdr, float* row_loss, hipStream_t s) {
+                   int zero_pad, int64_t ignore_index, DeviceHeader* hdr, float* row_loss,
+                   hipStream_t s) {
     const bool vec = aligned(Z, 16) && ((ldz * sizeof(T)) % 16 == 0);
     ScopedKernelTimer timer(FLCE_KIND_CE_ROWS, s);
     // rows from 96 KB on: the 1024-thread kernel that keeps the first 256 KB of the row in
@@ -166,14 +169,14 @@ int launch_ce_rows(T* Z, int64_t ldz, const int64_t* targets, int64_t rows, int6
     // the 256-thread kernel's higher occupancy wins)
     if (vec && V * (int64_t)sizeof(T) >= 98304)
         hipLaunchKernelGGL((ce_rows_cached_kernel<T>), dim3((unsigned)rows), dim3(RC_THREADS), 0, s, Z,
-                           ldz, targets, (int)V, ignore_index, hdr, row_loss);
+                           ldz, targets, (int)V, zero_pad, ignore_index, hdr, row_loss);
     else if (vec)
         hipLaunchKernelGGL((ce_rows_inplace_kernel<T, true>), dim3((unsigned)rows), dim3(RR_THREADS),
-                           0, s, Z, ldz, targets, (int)V, ignore_index, hdr, row_loss);
+                           0, s, Z, ldz, targets, (int)V, zero_pad, ignore_index, hdr, row_loss);
     else
         hipLaunchKernelGGL((ce_rows_inplace_kernel<T, false>), dim3((unsigned)rows),
-                           dim3(RR_THREADS), 0, s, Z, ldz, targets, (int)V, ignore_index, hdr,
-                           row_loss);
+                           dim3(RR_THREADS), 0, s, Z, ldz, targets, (int)V, zero_pad, ignore_index,
+                           hdr, row_loss);
     HIP_TRY(hipGetLastError());
     hipLaunchKernelGGL(loss_accumulate_kernel, dim3(1), dim3(256), 0, s, row_loss, (int)rows, hdr);
     HIP_TRY(hipGetLastError());
@@ -254,7 +257,8 @@ int run_head(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t
         }
 
         // loss and in-place dlogits
-        FLCE_TRY(launch_ce_rows<T>(Z, p.ldz, targets + r0, rows, V, ignore_index, hdr, row_loss, s));
+        FLCE_TRY(launch_ce_rows<T>(Z, p.ldz, targets + r0, rows, V, (int)(p.ldz - V), ignore_index, hdr,
+                                   row_loss, s));
 
         // dX_c (+)= G W
         if (want_dx) {
@@ -533,10 +537,10 @@ int flce_cross_entropy_inplace(void* Z, const int64_t* targets, int64_t BT, int6
         const int64_t rows = (BT - r0 < step) ? BT - r0 : step;
         if (dtype == FLCE_F32)
             FLCE_TRY(launch_ce_rows<float>(static_cast<float*>(Z) + r0 * ldz, ldz, targets + r0,
-                                           rows, V, ignore_index, hdr, row_loss, s));
+                                           rows, V, 0, ignore_index, hdr, row_loss, s));
         else
             FLCE_TRY(launch_ce_rows<bf16_t>(static_cast<bf16_t*>(Z) + r0 * ldz, ldz, targets + r0,
-                                            rows, V, ignore_index, hdr, row_loss, s));
+                                            rows, V, 0, ignore_index, hdr, row_loss, s));
     }
     HeadWeights one{};
     one.w[0] = 1.0f;

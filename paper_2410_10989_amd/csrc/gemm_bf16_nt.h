@@ -46,12 +46,15 @@
 // workgroups; piece s writes its partial result to C + s * split_stride (fp32), and a
 // separate fixed-order reduction adds the pieces (used when M x N has fewer tiles
 // than the chip has CUs, as for dX with its very long K = V).
-// Requirements (checked on the host): K % 64 == 0, leading dimensions % 8 == 0,
-// A and B 16-byte aligned, the byte extent of one tile below 2^30 (row form:
-// 256 * ld * 2 + 128, column form: 64 * ld * 2 + 512; operands themselves may be of
-// any size), 256 * ldc * sizeof(element) < 2^31 for C and Cin.  M and N are arbitrary:
-// tile rows / columns past them hold zeros or stale values and only feed outputs
-// that are never stored.
+// Requirements (checked on the host): leading dimensions % 8 == 0, A and B 16-byte
+// aligned, the byte extent of one tile below 2^30 (row form: 256 * ld * 2 + 128,
+// column form: 64 * ld * 2 + 512; operands themselves may be of any size),
+// 256 * ldc * sizeof(element) < 2^31 for C and Cin.  M and N are arbitrary: tile rows /
+// columns past them hold zeros or stale values and only feed outputs that are never
+// stored.  K is arbitrary for a column-form operand (its K rows past K lie outside the
+// descriptor's range and read as zero); a row-form operand needs K % 64 == 0, or rows
+// that are allocated up to the next multiple of 64 and hold zeros there (the dlogits
+// chunk is kept that way); the last K step then multiplies zeros.
 #pragma once
 #include <type_traits>
 
@@ -381,7 +384,7 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
     };
 
     // K steps [k_begin, k_begin + nk) belong to this workgroup
-    const int steps_all = a.K / FG_BK;
+    const int steps_all = (a.K + FG_BK - 1) / FG_BK;
     const int k_begin = (int)((int64_t)steps_all * split / a.ksplit);
     const int nk = (int)((int64_t)steps_all * (split + 1) / a.ksplit) - k_begin;
     opa.start_at(k_begin);

@@ -158,7 +158,7 @@ __device__ __forceinline__ float row_lse(MaxSum a, const T* z, int64_t t, int ro
 
 template <typename T, bool VEC16>
 __global__ __launch_bounds__(RR_THREADS) void ce_rows_inplace_kernel(
-    T* __restrict__ Z, int64_t ldz, const int64_t* __restrict__ targets, int V,
+    T* __restrict__ Z, int64_t ldz, const int64_t* __restrict__ targets, int V, int zero_pad,
     int64_t ignore_index, const DeviceHeader* __restrict__ hdr, float* __restrict__ row_loss) {
     constexpr int VEC = RowVec<T>::N;
     const int row = blockIdx.x;
@@ -172,6 +172,7 @@ __global__ __launch_bounds__(RR_THREADS) void ce_rows_inplace_kernel(
     __shared__ float s_lse;
 
     const int nvec = VEC16 ? V / VEC : 0;
+    if (tid < zero_pad) z[V + tid] = from_f32<T>(0.f);   // zero_pad < 64
     if (!valid) {   // uniform per workgroup
         const u32x4 zero = {0u, 0u, 0u, 0u};
         for (int i = tid; i < nvec; i += RR_THREADS) zv[i] = zero;
@@ -215,7 +216,7 @@ constexpr int RC_NV = 16;
 
 template <typename T>
 __global__ __launch_bounds__(RC_THREADS) void ce_rows_cached_kernel(
-    T* __restrict__ Z, int64_t ldz, const int64_t* __restrict__ targets, int V,
+    T* __restrict__ Z, int64_t ldz, const int64_t* __restrict__ targets, int V, int zero_pad,
     int64_t ignore_index, const DeviceHeader* __restrict__ hdr, float* __restrict__ row_loss) {
     constexpr int VEC = RowVec<T>::N;
     const int row = blockIdx.x;
@@ -229,6 +230,7 @@ __global__ __launch_bounds__(RC_THREADS) void ce_rows_cached_kernel(
     __shared__ MaxSum part[RC_THREADS / WAVE];
     __shared__ float s_lse;
 
+    if (tid < zero_pad) z[V + tid] = from_f32<T>(0.f);   // zero_pad < 64
     if (!valid) {                              // uniform per workgroup
         const u32x4 zero = {0u, 0u, 0u, 0u};
         for (int i = tid; i < nvec; i += RC_THREADS) zv[i] = zero;

@@ -96,18 +96,19 @@ inline Plan make_plan(int64_t BT, int64_t H, int64_t V, int dtype, size_t budget
     if (dtype != 0) {
         const bool out_ok = 256 * H * 4 < ((int64_t)1 << 31);
         p.fast_logits = (H % 64 == 0) && fits_row_form(H, H) && 256 * p.ldz * 2 < ((int64_t)1 << 31);
-        p.fast_dx = (V % 64 == 0) && (H % 8 == 0) && fits_row_form(p.ldz, V) && fits_col_form(H, V) &&
-                    out_ok;
+        // K of the dX product is V: the dlogits rows are padded with zeros to ldz, W is read
+        // K-major; K of the dW product is the chunk's row count, both operands K-major: any
+        // V and any row count do
+        p.fast_dx = (H % 8 == 0) && fits_row_form(p.ldz, V) && fits_col_form(H, V) && out_ok;
         auto dw_ok = [&](int64_t rows) {
-            return (rows % 64 == 0) && (H % 8 == 0) && fits_col_form(p.ldz, rows) &&
-                   fits_col_form(H, rows) && out_ok;
+            return (H % 8 == 0) && fits_col_form(p.ldz, rows) && fits_col_form(H, rows) && out_ok;
         };
         p.fast_dw_full = (p.nchunks > 1) ? dw_ok(p.C) : dw_ok(rows_last);
         p.fast_dw_last = dw_ok(rows_last);
     }
     if (p.fast_dx) {
         const int64_t rows = p.nchunks > 1 ? p.C : rows_last;
-        p.dx_ksplit = choose_ksplit(((rows + 255) / 256) * ((H + 255) / 256), V / 64,
+        p.dx_ksplit = choose_ksplit(((rows + 255) / 256) * ((H + 255) / 256), (V + 63) / 64,
                                     max_dx_ranges(budget_bytes, round_up(rows, 256), H));
     }
     const bool need_wt = !p.fast_dx;
@@ -130,7 +131,7 @@ inline Plan make_plan(int64_t BT, int64_t H, int64_t V, int dtype, size_t budget
     if (worst_case_bt && p.fast_dx) {
         // the bound has to hold for every chunk size the scheduler can pick
         for (int64_t c = CHUNK_ALIGN; c <= cmax; c += CHUNK_ALIGN) {
-            const int ks = choose_ksplit((c / 256) * ((H + 255) / 256), V / 64,
+            const int ks = choose_ksplit((c / 256) * ((H + 255) / 256), (V + 63) / 64,
                                          max_dx_ranges(budget_bytes, c, H));
             if (ks > 1) dxpart = std::max(dxpart, (size_t)ks * c * H * sizeof(float));
         }

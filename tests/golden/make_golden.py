@@ -7,6 +7,7 @@ vocabulary ids (full fp64 oracle arithmetic; stored as float32, which costs
 6e-8 relative, far below the parity tolerance).
 
     python tests/golden/make_golden.py [config ...]      # default: 2 3 4 5
+    python tests/golden/make_golden.py rmsnorm3          # RMSNorm in front of config 3
 """
 import os
 import sys
@@ -41,7 +42,31 @@ def sample_indices(w):
     return rows, vocab
 
 
+RMSNORM_EPS = 1e-5
+
+
+def rmsnorm_reference(idx):
+    """RMSNorm + projection + cross entropy on workload idx: loss, dgamma (needs the
+    whole dX), dh for the sampled rows, dW for the sampled vocabulary ids."""
+    t0 = time.time()
+    w = workloads.make_config(idx)
+    h, gamma = workloads.make_rmsnorm_inputs(w)
+    rows, vocab = sample_indices(w)
+    r = flce_oracle.rmsnorm_flce(h.astype(np.float64), gamma.astype(np.float64), RMSNORM_EPS,
+                                 w.W.astype(np.float64), w.targets, w.ignore_index, vocab=vocab)
+    out = os.path.join(HERE, f"rmsnorm_config{idx}_{w.name}.npz")
+    np.savez_compressed(out, loss=np.float64(r.loss), rows=rows, vocab=vocab, eps=np.float64(RMSNORM_EPS),
+                        dh_rows=r.dh[rows].astype(np.float32), dW_rows=r.dW.astype(np.float32),
+                        dgamma=r.dgamma.astype(np.float32),
+                        dh_absmax=np.float64(np.abs(r.dh).max()), checksum=workloads.checksum(w),
+                        h_sum=np.float64(h.astype(np.float64).sum()), gamma_sum=np.float64(gamma.sum()))
+    print(f"rmsnorm config {idx}: loss={r.loss:.12f} -> {out} ({os.path.getsize(out) / 1e6:.2f} MB, "
+          f"{time.time() - t0:.0f} s)", flush=True)
+
+
 def main(argv):
+    if argv and argv[0].startswith("rmsnorm"):
+        return rmsnorm_reference(int(argv[0][len("rmsnorm"):]))
     configs = [int(a) for a in argv] or [2, 3, 4, 5]
     for idx in configs:
         t0 = time.time()

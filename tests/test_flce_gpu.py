@@ -46,6 +46,9 @@ def test_config1_tiny_fp32():
     (768, 320, 1344, ("iid", 0.1)),     # tuned-kernel path: K multiples of 64, ragged tile edges
     (256, 64, 256, ("none",)),          # tuned-kernel path: exactly one macro tile
     (832, 192, 2112, ("iid", 0.5)),     # tuned-kernel path, half the rows ignored
+    (520, 256, 3001, ("iid", 0.1)),     # tuned kernels with V % 64 != 0: zero-padded K tail of dX
+    (1000, 128, 50257 // 8, ("iid", 0.1)),   # odd V (a GPT-2 style vocabulary, scaled down) and rows % 64 != 0
+    (70, 64, 65, ("none",)),            # one column past a K step; fewer rows than a K step
 ])
 def test_ragged_shapes(dtype, BT, H, V, ignore):
     check_full(workloads.make(BT, H, V, dtype, ignore=ignore, seed=1000 + BT + V, name="ragged"))
@@ -133,3 +136,17 @@ def test_standalone_cross_entropy(dtype, BT, V, pad):
     assert_close("dZ", to_host(view), ref_G, rg)
     if pad:
         assert (to_host(buf[:, V:]) == 0).all()   # the row padding is not touched
+
+
+def test_ragged_vocabulary_with_a_poisoned_workspace():
+    # V % 64 != 0: the dX product reads the dlogits rows up to the next multiple of 64; those
+    # padding columns must have been set to zero, whatever the lent workspace held before
+    import paper_2410_10989_amd as flce
+    w = workloads.make(384, 128, 1000, "bf16", ignore=("iid", 0.1), seed=64, name="poisoned_ws")
+    need = flce.flce_workspace_bytes(w.BT, w.H, w.V, flce.FLCE_BF16)
+    ws = torch.full((need // 2 + 128,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    try:
+        flce.flce_set_workspace(ws)
+        check_full(w)
+    finally:
+        flce.flce_set_workspace(None)

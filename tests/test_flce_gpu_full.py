@@ -101,3 +101,65 @@ def test_budget_change_leaves_headline_result_within_tolerance():
         assert abs(o[0] - outs[0][0]) <= 1e-6 * abs(outs[0][0])
         assert torch.equal(o[1], outs[0][1])          # dX rows never mix chunks
         assert (o[2] - outs[0][2]).abs().max().item() <= 1e-2 * outs[0][2].abs().max().item()
+
+
+def test_full_size_two_heads_against_stored_oracle():
+    # Two heads with the SAME weight and targets and loss weights 0.75 / 0.25: by linearity the
+    # loss and dX are the single-head ones and dW_j is weight_j times the single-head dW, so the
+    # stored config-3 reference covers the multi-head entry point at full size (dX summed over
+    # heads through the bf16 addend of the dX product, per-head scaling of the gradients).
+    import paper_2410_10989_amd as flce
+    name = workloads.CONFIGS[2]["name"]
+    ref = np.load(os.path.join(GOLDEN, f"config3_{name}.npz"))
+    w = workloads.make_config(3)
+    assert workloads.checksum(w) == str(ref["checksum"])
+    X, W, t = upload(w)
+    nan = float("nan")
+    dX = torch.full_like(X, nan)
+    dWs = [torch.full_like(W, nan), torch.full_like(W, nan)]
+    wts = [0.75, 0.25]
+    loss, hl, _, _ = flce.flce_multihead_fwd_bwd(X, [W, W], [t, t], wts, w.ignore_index, dX=dX, dWs=dWs)
+    torch.cuda.synchronize()
+    rl, rg = TOL["bf16"]
+    assert_loss(float(loss.item()), float(ref["loss"]), rl)
+    for v in hl.tolist():
+        assert_loss(v, float(ref["loss"]), rl)
+    rows = torch.from_numpy(ref["rows"]).cuda()
+    vocab = torch.from_numpy(ref["vocab"]).cuda()
+    assert_close("dX[sampled rows]", to_host(dX[rows]), ref["dX_rows"].astype(np.float64), rg)
+    for wt, dW in zip(wts, dWs):
+        assert_close("dW[sampled vocab]", to_host(dW[vocab]), wt * ref["dW_rows"].astype(np.float64), rg)
+    assert torch.isfinite(dX).all() and all(torch.isfinite(d).all() for d in dWs)
+    assert (dX[t == w.ignore_index] == 0).all()
+
+
+def test_full_size_rmsnorm_against_stored_oracle():
+    import paper_2410_10989_amd as flce
+    from flce_testlib import to_device
+    name = workloads.CONFIGS[2]["name"]
+    ref = np.load(os.path.join(GOLDEN, f"rmsnorm_config3_{name}.npz"))
+    w = workloads.make_config(3)
+    assert workloads.checksum(w) == str(ref["checksum"])
+    h, gamma = workloads.make_rmsnorm_inputs(w)
+    assert abs(h.astype(np.float64).sum() - float(ref["h_sum"])) <= 1e-9 * abs(float(ref["h_sum"]))
+    assert abs(float(gamma.sum()) - float(ref["gamma_sum"])) <= 1e-6
+    hd, gd, Wd = to_device(h, "bf16"), to_device(gamma, "bf16"), to_device(w.W, "bf16")
+    t = torch.from_numpy(w.targets).cuda()
+    nan = float("nan")
+    dh, dg, dW = torch.full_like(hd, nan), torch.full_like(gd, nan), torch.full_like(Wd, nan)
+    loss = torch.full((), nan, dtype=torch.float32, device="cuda")
+    flce.flce_rmsnorm_fwd_bwd(hd, gd, float(ref["eps"]), Wd, t, w.ignore_index, loss=loss, dh=dh,
+                              dgamma=dg, dW=dW)
+    torch.cuda.synchronize()
+    rl, rg = TOL["bf16"]
+    assert_loss(float(loss.item()), float(ref["loss"]), rl)
+    rows = torch.from_numpy(ref["rows"]).cuda()
+    vocab = torch.from_numpy(ref["vocab"]).cuda()
+    # dh rows differ in scale by the row factors, so the bar is relative to the largest entry of
+    # the whole dh, which the reference stores
+    assert_close("dh[sampled rows]", to_host(dh[rows]), ref["dh_rows"].astype(np.float64), rg,
+                 ref_max=float(ref["dh_absmax"]))
+    assert_close("dW[sampled vocab]", to_host(dW[vocab]), ref["dW_rows"].astype(np.float64), rg)
+    assert_close("dgamma", to_host(dg), ref["dgamma"].astype(np.float64), rg)
+    assert torch.isfinite(dh).all() and torch.isfinite(dW).all()
+    assert (dh[t == w.ignore_index] == 0).all()

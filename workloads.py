@@ -173,6 +173,20 @@ def make_multihead(n_heads, BT, H, V, seq, dtype="bf16", targets="uniform", igno
     return MultiHeadWorkload(base, Ws, ts, [float(decay) ** j for j in range(n_heads)])
 
 
+def make_rmsnorm_inputs(w: Workload):
+    """Raw hidden states and RMSNorm scale for workload w: h = w.X times a
+    log-normal factor per row (tensor id 32), gamma = 1 + 0.1 N(0,1) (tensor id
+    33), both rounded to w's storage type.  Returns (h, gamma) as float32."""
+    g = _rng(w.seed, 32)
+    scale = np.exp(0.5 * g.standard_normal(w.BT)).astype(np.float32)
+    h = w.X * scale[:, None]
+    gamma = (1.0 + 0.1 * _rng(w.seed, 33).standard_normal(w.H)).astype(np.float32)
+    if w.dtype == "bf16":
+        round_to_bf16(h)
+        round_to_bf16(gamma)
+    return h, gamma
+
+
 def make_config(index: int, BT: int | None = None) -> Workload:
     """Workload `index` (1-based, the order of the benchmark's config list).
     `BT` overrides the row count (used for bounded samples and BT sweeps)."""
