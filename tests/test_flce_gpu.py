@@ -150,3 +150,40 @@ def test_ragged_vocabulary_with_a_poisoned_workspace():
         check_full(w)
     finally:
         flce.flce_set_workspace(None)
+
+
+def test_lent_workspace_that_is_too_small_is_refused():
+    import paper_2410_10989_amd as flce
+    w = workloads.make(256, 128, 1024, "bf16", seed=3, name="small_ws")
+    X, W, t = upload(w)
+    ws = torch.empty(4096, dtype=torch.uint8, device="cuda")
+    try:
+        flce.flce_set_workspace(ws)
+        with pytest.raises(flce.FlceError) as e:
+            flce.flce_fwd_bwd(X, W, t, w.ignore_index)
+        assert e.value.status == 5
+    finally:
+        flce.flce_set_workspace(None)
+    check_full(w)   # and the library-owned workspace still works afterwards
+
+
+def test_call_on_a_side_stream_is_ordered_with_that_stream():
+    # the whole call is enqueued on the caller's stream: work queued before it on that stream
+    # (here: the upload-side fill of X) is seen, and a stream synchronise is all the caller needs
+    import paper_2410_10989_amd as flce
+    w = workloads.make(640, 256, 2048, "bf16", ignore=("iid", 0.1), seed=17, name="side_stream")
+    ref = oracle.flce(w.X, w.W, w.targets, w.ignore_index)
+    Xh, W, t = upload(w)
+    side = torch.cuda.Stream()
+    X = torch.empty_like(Xh)
+    dX, dW = torch.empty_like(Xh), torch.empty_like(W)
+    loss = torch.empty((), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        X.copy_(Xh, non_blocking=True)
+        flce.flce_fwd_bwd(X, W, t, w.ignore_index, loss=loss, dX=dX, dW=dW)   # current stream = side
+    side.synchronize()
+    rl, rg = TOL["bf16"]
+    assert_loss(float(loss.item()), ref.loss, rl)
+    assert_close("dX", to_host(dX), ref.dX, rg)
+    assert_close("dW", to_host(dW), ref.dW, rg)
