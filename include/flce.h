@@ -39,6 +39,11 @@
  *    growing synchronises the device).  Calls that overlap in time on the same
  *    device share the workspace and therefore race: serialise them on one
  *    stream.
+ *  - Once the workspace is large enough (after a first call of the same size, or
+ *    with a lent buffer) a call consists of kernel launches on `stream` only: no
+ *    allocation, no memset, no synchronisation.  It can therefore be recorded
+ *    into a HIP graph by stream capture and replayed (not while
+ *    flce_timing_enable is on).
  */
 #ifndef FLCE_H
 #define FLCE_H

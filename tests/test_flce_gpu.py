@@ -187,3 +187,38 @@ def test_call_on_a_side_stream_is_ordered_with_that_stream():
     assert_loss(float(loss.item()), ref.loss, rl)
     assert_close("dX", to_host(dX), ref.dX, rg)
     assert_close("dW", to_host(dW), ref.dW, rg)
+
+
+def test_call_can_be_captured_in_a_graph_and_replayed():
+    # The call is kernel launches on the caller's stream only (no allocation once the workspace
+    # exists, no memset, no synchronisation), so it can be recorded into a HIP graph.  Every
+    # replay, with the program's own eager work in between, must give the eager result's bits.
+    import paper_2410_10989_amd as flce
+    w = workloads.make(513, 192, 1536, "bf16", ignore=("iid", 0.1), seed=23, name="graph")
+    X0, W, t = upload(w)
+    old = flce.flce_get_logits_budget_bytes()
+    try:
+        flce.flce_set_logits_budget_bytes(256 * 1536 * 2)      # 3 chunks: the whole loop is captured
+        X = X0.clone()
+        loss = torch.empty((), dtype=torch.float32, device="cuda")
+        dX, dW = torch.empty_like(X), torch.empty_like(W)
+        flce.flce_fwd_bwd(X, W, t, w.ignore_index, loss=loss, dX=dX, dW=dW)   # sizes the workspace
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            flce.flce_fwd_bwd(X, W, t, w.ignore_index, loss=loss, dX=dX, dW=dW)
+        for scale in (1.0, 0.5, -2.0, 1.0):
+            X.copy_(X0 * scale)
+            dX.fill_(float("nan"))
+            dW.fill_(float("nan"))
+            loss.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            got = (loss.item(), dX.clone(), dW.clone())
+            e_loss, e_dX, e_dW = flce.flce_fwd_bwd(X, W, t, w.ignore_index)   # eager, fresh outputs
+            torch.cuda.synchronize()
+            assert got[0] == e_loss.item()
+            assert torch.equal(got[1].view(torch.int16), e_dX.view(torch.int16))
+            assert torch.equal(got[2].view(torch.int16), e_dW.view(torch.int16))
+    finally:
+        flce.flce_set_logits_budget_bytes(old)
