@@ -190,6 +190,10 @@ FLCE_API size_t flce_get_logits_budget_bytes(void);
 FLCE_API int64_t flce_chunk_rows(int64_t BT, int64_t H, int64_t V, int dtype);
 FLCE_API int64_t flce_num_chunks(int64_t BT, int64_t H, int64_t V, int dtype);
 
+/* Number of K ranges (K = V) the dX product of one chunk is cut into so that its
+ * output tiles fill whole rounds of the chip's CUs; 1 = not cut (host only). */
+FLCE_API int flce_dx_k_ranges(int64_t BT, int64_t H, int64_t V, int dtype);
+
 /* The paper's own chunk-size rule, 2^ceil(log2(ceil(BT / ceil(V/H)))), for
  * reference and reporting; the scheduler above does not use it. */
 FLCE_API int64_t flce_paper_chunk_rows(int64_t BT, int64_t H, int64_t V);

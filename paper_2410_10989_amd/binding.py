@@ -49,6 +49,7 @@ def lib() -> ctypes.CDLL:
             "flce_get_logits_budget_bytes": ([], sz),
             "flce_chunk_rows": ([i64, i64, i64, ci], i64),
             "flce_num_chunks": ([i64, i64, i64, ci], i64),
+            "flce_dx_k_ranges": ([i64, i64, i64, ci], ci),
             "flce_paper_chunk_rows": ([i64, i64, i64], i64),
             "flce_full_logits_bytes": ([i64, i64, ci], sz),
             "flce_timing_enable": ([ci], ci),
@@ -269,6 +270,10 @@ def flce_chunk_rows(BT, H, V, dtype) -> int:
 
 def flce_num_chunks(BT, H, V, dtype) -> int:
     return int(lib().flce_num_chunks(BT, H, V, _DTYPES.get(dtype, dtype)))
+
+
+def flce_dx_k_ranges(BT, H, V, dtype) -> int:
+    return int(lib().flce_dx_k_ranges(BT, H, V, _DTYPES.get(dtype, dtype)))
 
 
 def flce_paper_chunk_rows(BT, H, V) -> int:

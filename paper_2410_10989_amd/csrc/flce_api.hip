@@ -605,6 +605,11 @@ int64_t flce_num_chunks(int64_t BT, int64_t H, int64_t V, int dtype) {
     return make_plan(BT, H, V, dtype, g_budget).nchunks;
 }
 
+int flce_dx_k_ranges(int64_t BT, int64_t H, int64_t V, int dtype) {
+    if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
+    return make_plan(BT, H, V, dtype, g_budget).dx_ksplit;
+}
+
 int64_t flce_paper_chunk_rows(int64_t BT, int64_t H, int64_t V) {
     if (BT <= 0 || H <= 0 || V <= 0) return 0;
     return paper_chunk_rows(BT, H, V);

@@ -67,6 +67,23 @@ def test_workspace_is_bounded_independently_of_BT(H, V):
         assert flce.flce_workspace_bytes(bt, H, V, code) <= cap
 
 
+def test_dx_product_is_cut_along_k_to_fill_whole_rounds_of_cus():
+    code = flce.FLCE_BF16
+    k = flce.flce_dx_k_ranges
+    assert k(8192, 4096, 128256, code) == 1       # 2 chunks of 4096 rows: 16 x 16 = 256 tiles, one full round
+    assert k(4352, 4096, 8192, code) == 2         # 272 tiles, K = 128 steps: at most 2 ranges of 64 steps
+    assert k(16384, 3584, 152064, code) >= 4      # chunks of 3328 rows: 13 x 14 = 182 tiles
+    assert k(8192, 2304, 256000, code) >= 3       # chunks of 2048 rows: 8 x 9 = 72 tiles
+    assert k(65536, 4096, 32000, code) == 1       # 16384-row chunks: 1024 tiles, many rounds
+    assert k(256, 512, 4096, flce.FLCE_F32) == 1  # fp32 storage runs on the guarded kernels
+    for bt, h, v in [(4352, 4096, 8192), (16384, 3584, 152064), (8192, 2304, 256000)]:
+        # the fp32 partial results are part of the reported workspace and stay within the budget
+        c = flce.flce_chunk_rows(bt, h, v, code)
+        part = k(bt, h, v, code) * c * h * 4
+        assert part <= flce.flce_get_logits_budget_bytes()
+        assert flce.flce_workspace_bytes(bt, h, v, code) >= part
+
+
 def test_bad_arguments_are_rejected_on_the_host():
     L = flce.lib()
     buf = (ctypes.c_char * 4096)()
