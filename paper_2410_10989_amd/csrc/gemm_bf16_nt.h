@@ -443,43 +443,45 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
     const int uwm = __builtin_amdgcn_readfirstlane(wm), uwn = __builtin_amdgcn_readfirstlane(wn);
     const int lane_off = (4 * fhalf * ldc + frow) * ES;
     const int lane_off_in = (4 * fhalf * ldcin + frow) * IS;
+    // Addend of one 32 x 32 tile of this wavefront (16 loads); issued one tile ahead of
+    // its use so that the loads' latency hides behind the previous tile's stores.
+    auto load_addend = [&](int t, float (&old)[16]) __attribute__((always_inline)) {
+        const int i = t & 3, j = t >> 2;
+        const int row0 = uwm * 128 + i * 32, col0 = n0 + uwn * 128 + j * 32;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int col0 = n0 + uwn * 128 + j * 32;
+        for (int g = 0; g < 16; ++g) {
+            const int soff = ((row0 + 8 * (g >> 2) + (g & 3)) * ldcin + col0) * IS;
+            if constexpr (IS == 4)
+                old[g] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc_in, lane_off_in, soff, 0));
+            else   // bf16 addend: its 16 bits are the high half of the float
+                old[g] = __uint_as_float(
+                    (unsigned)__builtin_amdgcn_raw_buffer_load_b16(rsrc_in, lane_off_in, soff, 0) << 16);
+        }
+    };
+    float old[2][16];
+    if constexpr (HAS_IN) load_addend(0, old[0]);
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {   // tile t: i = t % 4 (rows), j = t / 4 (columns)
+        const int i = t & 3, j = t >> 2;
+        const int row0 = uwm * 128 + i * 32, col0 = n0 + uwn * 128 + j * 32;
+        if constexpr (HAS_IN) {
+            if (t + 1 < 16) load_addend(t + 1, old[(t + 1) & 1]);
+#pragma unroll
+            for (int g = 0; g < 16; ++g) acc[i][j][g] += old[t & 1][g];
+        }
         if (col0 + frow < a.N) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int row0 = uwm * 128 + i * 32;
-                if constexpr (HAS_IN) {
-                    float old[16];
-#pragma unroll
-                    for (int g = 0; g < 16; ++g) {
-                        const int soff = ((row0 + 8 * (g >> 2) + (g & 3)) * ldcin + col0) * IS;
-                        if constexpr (IS == 4)
-                            old[g] = __uint_as_float(
-                                __builtin_amdgcn_raw_buffer_load_b32(rsrc_in, lane_off_in, soff, 0));
-                        else   // bf16 addend: its 16 bits are the high half of the float
-                            old[g] = __uint_as_float(
-                                (unsigned)__builtin_amdgcn_raw_buffer_load_b16(rsrc_in, lane_off_in, soff, 0)
-                                << 16);
-                    }
-#pragma unroll
-                    for (int g = 0; g < 16; ++g) acc[i][j][g] += old[g];
-                }
-#pragma unroll
-                for (int g = 0; g < 16; ++g) {
-                    const int soff = ((row0 + 8 * (g >> 2) + (g & 3)) * ldc + col0) * ES;
-                    // read the element into a scalar first: a bit_cast applied directly
-                    // to an accumulator vector element is miscompiled by this toolchain
-                    const float v = acc[i][j][g];
-                    if constexpr (ES == 4) {
-                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rsrc_c, lane_off, soff,
-                                                              0);
-                    } else {
-                        __builtin_amdgcn_raw_buffer_store_b16(
-                            __builtin_bit_cast(unsigned short, from_f32<bf16_t>(v)), rsrc_c, lane_off,
-                            soff, 0);
-                    }
+            for (int g = 0; g < 16; ++g) {
+                const int soff = ((row0 + 8 * (g >> 2) + (g & 3)) * ldc + col0) * ES;
+                // read the element into a scalar first: a bit_cast applied directly
+                // to an accumulator vector element is miscompiled by this toolchain
+                const float v = acc[i][j][g];
+                if constexpr (ES == 4) {
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rsrc_c, lane_off, soff, 0);
+                } else {
+                    __builtin_amdgcn_raw_buffer_store_b16(
+                        __builtin_bit_cast(unsigned short, from_f32<bf16_t>(v)), rsrc_c, lane_off, soff,
+                        0);
                 }
             }
         }
