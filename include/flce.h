@@ -25,6 +25,10 @@
  *    are fully overwritten (rows of dX whose target is ignored become 0).
  *  - dtype selects the storage type of X, W, dX, dW (flce_dtype).  Products
  *    accumulate in fp32; the reduction math is fp32; loss is fp32.
+ *  - Any BT, H, V >= 1 (each below 2^30) are accepted.  bf16 problems with
+ *    H % 64 == 0 run entirely on the tuned matrix-core kernel, whatever BT and V
+ *    are; other H and fp32 storage run on slower, fully guarded kernels and need
+ *    more workspace (transposed copies); the results meet the same bars.
  *  - Targets must lie in [0, V) or equal ignore_index; anything else is a
  *    precondition violation (not detected: checking would need a host sync).
  *  - N == 0 gives loss = 0, dX = 0, dW = 0.
