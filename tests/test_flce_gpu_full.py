@@ -163,3 +163,37 @@ def test_full_size_rmsnorm_against_stored_oracle():
     assert_close("dgamma", to_host(dg), ref["dgamma"].astype(np.float64), rg)
     assert torch.isfinite(dh).all() and torch.isfinite(dW).all()
     assert (dh[t == w.ignore_index] == 0).all()
+
+
+def test_extra_device_memory_does_not_grow_with_BT():
+    # At the Llama-3 head: the library-owned workspace, measured through the driver's free-memory
+    # counter around each call (all tensors are allocated before), is what flce_workspace_bytes
+    # reports, is allocated by the first call, and serves 2, 4 and 8 chunks of rows unchanged
+    # (the full logits would be 2.1, 4.2 and 8.4 GB).
+    import paper_2410_10989_amd as flce
+    H, V = 4096, 128256
+    code = flce.FLCE_BF16
+    flce.flce_release_workspace()
+    W = (torch.randn(V, H, device="cuda") * 0.02).to(torch.bfloat16)
+    dW = torch.empty_like(W)
+    C = flce.flce_chunk_rows(10 ** 7, H, V, code)
+    deltas = []
+    for BT in (2 * C, 4 * C, 8 * C):
+        g = torch.Generator(device="cuda").manual_seed(BT)
+        X = torch.randn(BT, H, device="cuda", generator=g).to(torch.bfloat16)
+        t = torch.randint(0, V, (BT,), device="cuda", generator=g)
+        dX = torch.empty_like(X)
+        loss = torch.empty((), dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()
+        free_before = torch.cuda.mem_get_info()[0]
+        flce.flce_fwd_bwd(X, W, t, loss=loss, dX=dX, dW=dW)
+        torch.cuda.synchronize()
+        deltas.append(free_before - torch.cuda.mem_get_info()[0])
+        assert math.isfinite(loss.item()) and abs(loss.item() - math.log(V)) < 1.0
+        assert flce.flce_workspace_bytes(BT, H, V, code) == flce.flce_workspace_bytes(2 * C, H, V, code)
+        assert flce.flce_workspace_bytes(BT, H, V, code) < flce.flce_full_logits_bytes(8 * C, V, code)
+        del X, dX, t, loss
+    print("  device memory taken by the three calls:", [d >> 20 for d in deltas], "MiB", flush=True)
+    assert abs(deltas[0] - flce.flce_workspace_bytes(2 * C, H, V, code)) <= 64 << 20
+    assert deltas[1] == 0 and deltas[2] == 0
+    flce.flce_release_workspace()
