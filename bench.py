@@ -173,12 +173,17 @@ def main():
     torch.cuda.synchronize()
 
     flce.flce_timing_enable(True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for k in range(args.steps):
         step()
+        marks[k + 1].record()      # same stream as the call: per-step times for the quantiles
     torch.cuda.synchronize()
     t2 = time.perf_counter()
+    per_step = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps))
+    quantile = lambda q: per_step[int(round(q * (len(per_step) - 1)))]
     flce.flce_timing_enable(False)
     kt = flce.flce_timing_collect()
     ms_per_step = (t2 - t1) * 1e3 / args.steps
@@ -211,6 +216,7 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": ms_per_step,
+        "ms_per_step_q20_median_q80": [quantile(0.2), quantile(0.5), quantile(0.8)],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
