@@ -98,6 +98,8 @@ def main():
                          "Medusa setting, section 4.2), timed through flce_multihead_fwd_bwd")
     ap.add_argument("--skip-dx", action="store_true",
                     help="frozen backbone (Medusa stage 1): no hidden-state gradient")
+    ap.add_argument("--no-compaction", action="store_true",
+                    help="project every row, also those with an ignored target (A/B of the row compaction)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one plain 1 GiB device copy first (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -118,6 +120,8 @@ def main():
         return bench_cross_entropy(args)
     if args.budget_mib:
         flce.flce_set_logits_budget_bytes(args.budget_mib << 20)
+    if args.no_compaction:
+        flce.flce_set_row_compaction(False)
 
     t0 = time.time()
     w = workloads.make_config(args.config)
@@ -168,6 +172,13 @@ def main():
             flce.flce_fwd_bwd(X, W, t, w.ignore_index, loss=loss, dX=None if args.skip_dx else dX,
                               dW=dW, flags=flags)
 
+    # rows that are actually projected: with row compaction (the default) only the rows that
+    # have a target, summed over the heads
+    all_targets = ts if nh > 1 else [t]
+    compaction = flce.flce_get_row_compaction() and w.dtype == "bf16" and w.H % 64 == 0
+    rows_projected = sum(int((x != w.ignore_index).sum().item()) for x in all_targets) if compaction \
+        else w.BT * nh
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -201,7 +212,8 @@ def main():
     symbols = {"logits_gemm": 1, "dx_gemm": 1, "dw_gemm": 2 if nchunks > 1 else 1}
     dom = max(gemm_kinds, key=lambda k: kt[k][0] / symbols[k])
     dom_ms, dom_n = kt[dom]
-    flops_per_launch = 2.0 * w.BT * w.H * w.V * nh * args.steps / max(dom_n, 1)   # mean over its launches
+    # executed flops of the dominant kernel, mean over its launches (ignored rows are not projected)
+    flops_per_launch = 2.0 * rows_projected * w.H * w.V * args.steps / max(dom_n, 1)
     dom_avg_ms = dom_ms / max(dom_n, 1)
     achieved = flops_per_launch / (dom_avg_ms * 1e-3) / 1e12 if dom_n else 0.0
     ce_ms, ce_n = kt["ce_rows"]
@@ -227,8 +239,13 @@ def main():
                    flce.flce_chunk_rows(w.BT, w.H, w.V, code), "chunks": nchunks,
                    "logits_budget_mib": flce.flce_get_logits_budget_bytes() >> 20},
         "heads": nh,
-        "tflops_over_6BTHV": tflops,   # over 6*BT*H*V per head (4*BT*H*V without dX)
+        "tflops_over_6BTHV": tflops,   # nominal: over 6*BT*H*V per head (4*BT*H*V without dX)
         "mfma_util_frac_of_peak": tflops / peak,
+        # rows with an ignored target are left out of the products (row compaction): what the
+        # matrix cores really executed is smaller than the nominal count by this share
+        "row_compaction": bool(compaction),
+        "rows_projected": rows_projected,
+        "tflops_executed": tflops * rows_projected / (w.BT * nh),
         "peak_extra_hbm_mb": flce.flce_workspace_bytes(w.BT, w.H, w.V, code) / 1e6,
         "full_logits_avoided_mb": flce.flce_full_logits_bytes(w.BT, w.V, code) / 1e6,
         "loss": float(loss.item()),

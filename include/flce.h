@@ -190,6 +190,17 @@ FLCE_API int flce_release_workspace(void);
 FLCE_API int flce_set_logits_budget_bytes(size_t bytes);
 FLCE_API size_t flce_get_logits_budget_bytes(void);
 
+/* Row compaction (default on).  Rows whose target is ignore_index add nothing to
+ * the loss or to dW and have a zero dX row, so each chunk first gathers its other
+ * rows into a dense block, runs the products and the row kernel on that block
+ * only, and scatters dX back; the chunk's live row count stays on the device (no
+ * host synchronisation).  The results are the same (dW sums the same non-zero
+ * terms in other groups); the time of a chunk shrinks with its share of ignored
+ * rows, in steps of the 256-row tiles.  Only problems that run entirely on the
+ * tuned kernel are compacted.  Off: every row is projected. */
+FLCE_API int flce_set_row_compaction(int on);
+FLCE_API int flce_get_row_compaction(void);
+
 /* Rows per chunk C and number of chunks the scheduler picks (host only). */
 FLCE_API int64_t flce_chunk_rows(int64_t BT, int64_t H, int64_t V, int dtype);
 FLCE_API int64_t flce_num_chunks(int64_t BT, int64_t H, int64_t V, int dtype);

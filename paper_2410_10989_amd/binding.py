@@ -47,6 +47,8 @@ def lib() -> ctypes.CDLL:
             "flce_release_workspace": ([], ci),
             "flce_set_logits_budget_bytes": ([sz], ci),
             "flce_get_logits_budget_bytes": ([], sz),
+            "flce_set_row_compaction": ([ci], ci),
+            "flce_get_row_compaction": ([], ci),
             "flce_chunk_rows": ([i64, i64, i64, ci], i64),
             "flce_num_chunks": ([i64, i64, i64, ci], i64),
             "flce_dx_k_ranges": ([i64, i64, i64, ci], ci),
@@ -262,6 +264,14 @@ def flce_set_logits_budget_bytes(n: int):
 
 def flce_get_logits_budget_bytes() -> int:
     return int(lib().flce_get_logits_budget_bytes())
+
+
+def flce_set_row_compaction(on: bool):
+    _check(lib().flce_set_row_compaction(1 if on else 0), "flce_set_row_compaction")
+
+
+def flce_get_row_compaction() -> bool:
+    return bool(lib().flce_get_row_compaction())
 
 
 def flce_chunk_rows(BT, H, V, dtype) -> int:

@@ -6,6 +6,7 @@
 #include <vector>
 
 #include "../../include/flce.h"
+#include "compact.h"
 #include "flce_device.h"
 #include "gemm_bf16_nt.h"
 #include "gemm_generic.h"
@@ -32,6 +33,7 @@ struct DeviceWorkspace {
 std::mutex g_mutex;
 DeviceWorkspace g_ws[MAX_DEVICES];
 size_t g_budget = (size_t)1 << 30;
+bool g_compact = true;
 
 // ---- optional per-kernel timing (benchmarks only) ----
 struct TimingRecord {
@@ -131,12 +133,14 @@ int launch_gemm_generic(int kind, const T* A, int64_t lda, const T* B, int64_t l
 template <typename OutT, typename InT, bool A_KM, bool B_KM>
 int launch_gemm_fast(int kind, const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, OutT* C,
                      int64_t ldc, const InT* Cin, int64_t ldcin, int64_t M, int64_t N, int64_t K,
-                     hipStream_t s, int ksplit = 1, int64_t split_stride = 0) {
+                     hipStream_t s, int ksplit = 1, int64_t split_stride = 0,
+                     const int* dyn_rows = nullptr, int dyn_is_k = 0) {
     if (M <= 0 || N <= 0 || K <= 0) return FLCE_OK;
     if (!aligned(A, 16) || !aligned(B, 16)) return FLCE_ERR_ARG;
     ScopedKernelTimer timer(kind, s);
     FGArgs a{A, lda, B, ldb, C, ldc, Cin, ldcin, (int)M, (int)N, (int)K,
-             (int)((M + FG_BM - 1) / FG_BM), (int)((N + FG_BN - 1) / FG_BN), ksplit, split_stride};
+             (int)((M + FG_BM - 1) / FG_BM), (int)((N + FG_BN - 1) / FG_BN), ksplit, split_stride,
+             dyn_rows, dyn_is_k};
     const int64_t total = (int64_t)a.tiles_m * a.tiles_n * ksplit;
     const dim3 grid((unsigned)((total + FG_XCDS - 1) / FG_XCDS * FG_XCDS));
     hipLaunchKernelGGL((gemm_bf16_256<OutT, InT, A_KM, B_KM>), grid, dim3(FG_THREADS), 0, s, a);
@@ -161,7 +165,7 @@ int launch_transpose(const T* in, int64_t ldin, T* out, int64_t ldout, int64_t R
 template <typename T>
 int launch_ce_rows(T* Z, int64_t ldz, const int64_t* targets, int64_t rows, int64_t V,
                    int zero_pad, int64_t ignore_index, DeviceHeader* hdr, float* row_loss,
-                   hipStream_t s) {
+                   hipStream_t s, const int* n_rows = nullptr) {
     const bool vec = aligned(Z, 16) && ((ldz * sizeof(T)) % 16 == 0);
     ScopedKernelTimer timer(FLCE_KIND_CE_ROWS, s);
     // rows from 96 KB on: the 1024-thread kernel that keeps the first 256 KB of the row in
@@ -169,14 +173,14 @@ int launch_ce_rows(T* Z, int64_t ldz, const int64_t* targets, int64_t rows, int6
     // the 256-thread kernel's higher occupancy wins)
     if (vec && V * (int64_t)sizeof(T) >= 98304)
         hipLaunchKernelGGL((ce_rows_cached_kernel<T>), dim3((unsigned)rows), dim3(RC_THREADS), 0, s, Z,
-                           ldz, targets, (int)V, zero_pad, ignore_index, hdr, row_loss);
+                           ldz, targets, (int)V, zero_pad, ignore_index, hdr, row_loss, n_rows);
     else if (vec)
         hipLaunchKernelGGL((ce_rows_inplace_kernel<T, true>), dim3((unsigned)rows), dim3(RR_THREADS),
-                           0, s, Z, ldz, targets, (int)V, zero_pad, ignore_index, hdr, row_loss);
+                           0, s, Z, ldz, targets, (int)V, zero_pad, ignore_index, hdr, row_loss, n_rows);
     else
         hipLaunchKernelGGL((ce_rows_inplace_kernel<T, false>), dim3((unsigned)rows),
                            dim3(RR_THREADS), 0, s, Z, ldz, targets, (int)V, zero_pad, ignore_index,
-                           hdr, row_loss);
+                           hdr, row_loss, n_rows);
     HIP_TRY(hipGetLastError());
     hipLaunchKernelGGL(loss_accumulate_kernel, dim3(1), dim3(256), 0, s, row_loss, (int)rows, hdr);
     HIP_TRY(hipGetLastError());
@@ -197,14 +201,13 @@ struct HeadWeights {
 };
 
 // RMSNorm in front of the projection: the chunk loop normalises each chunk of the
-// raw hidden states into Y just before its logits product and turns the chunk's
-// dX (left in dY) into the gradient of the raw hidden states right after.
+// raw hidden states just before its logits product (into the chunk buffer that
+// otherwise holds gathered rows) and turns the chunk's dX into the gradient of the
+// raw hidden states right after.
 template <typename T>
 struct NormCtx {
     const T* gamma;
     float eps;
-    T* Y;            // [C x H] normalised chunk
-    T* dY;           // [C x H] gradient w.r.t. the normalised chunk
     float* rstd;     // [C]
     float* partial;  // [RN_SLOTS x H] fp32 partial sums of dgamma, zero before the loop
     T* dh;           // [BT x H] out
@@ -226,43 +229,82 @@ int run_head(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t
     T* WT = reinterpret_cast<T*>(ws + p.off_wt);
     T* XT = reinterpret_cast<T*>(ws + p.off_xt);
     float* dWacc = reinterpret_cast<float*>(ws + p.off_dwacc);
+    T* Xg = reinterpret_cast<T*>(ws + p.off_xg);     // gathered (or normalised) rows of the chunk
+    T* dXg = reinterpret_cast<T*>(ws + p.off_dxg);   // their gradient
+    int* idx = reinterpret_cast<int*>(ws + p.off_idx);
+    int64_t* tv = reinterpret_cast<int64_t*>(ws + p.off_tv);
+    int* dyn = reinterpret_cast<int*>(ws + p.off_dyn);   // [0] row cursor, [1] live rows of the chunk
+    constexpr int VEC = 16 / (int)sizeof(T);
 
     hipLaunchKernelGGL(count_valid_kernel, dim3(1), dim3(1024), 0, s, targets, BT, ignore_index,
                        weight, hdr);
     HIP_TRY(hipGetLastError());
     if (want_dx && !p.fast_dx) FLCE_TRY(launch_transpose<T>(W, H, WT, p.ldz, V, H, s));   // WT[H x V]
+    if (p.compact && want_dx && !dx_add) {   // rows without a target: zero gradient
+        ScopedKernelTimer timer(FLCE_KIND_OTHER, s);
+        hipLaunchKernelGGL((zero_ignored_rows_kernel<T>), dim3((unsigned)(BT < 8192 ? BT : 8192)),
+                           dim3(256), 0, s, targets, BT, ignore_index, (int)H, norm ? norm->dh : dX);
+        HIP_TRY(hipGetLastError());
+    }
 
     bool dw_needs_cast = false;
     for (int64_t c = 0; c < p.nchunks; ++c) {
         const int64_t r0 = c * p.C;
         const int64_t rows = (BT - r0 < p.C) ? BT - r0 : p.C;
         const bool last = (c == p.nchunks - 1);
-        const T* Xc = X + r0 * H;
-        if (norm) {   // X holds the raw hidden states: normalise this chunk
+        // Compacted: the chunk is the next (at most) `rows` rows of the batch that have a
+        // target, wherever they are; Xc, Z and dXc hold *n_live rows (a device value), the
+        // launches below are sized for `rows`, and idx maps the chunk's rows to batch rows.
+        // Otherwise the chunk is rows r0 .. r0 + rows - 1 of the batch.
+        const int* n_live = p.compact ? dyn + 1 : nullptr;
+        const int* row_map = p.compact ? idx : nullptr;
+        const T* Xin = p.compact ? X : X + r0 * H;   // what the chunk's row indices refer to
+        const T* Xc = Xin;
+        const int64_t* tc = targets + r0;
+        if (p.compact) {
+            ScopedKernelTimer timer(FLCE_KIND_OTHER, s);
+            hipLaunchKernelGGL(compact_chunk_kernel, dim3(1), dim3(CP_THREADS), 0, s, targets, (int)BT,
+                               ignore_index, (int)rows, c == 0 ? 1 : 0, idx, tv, dyn);
+            HIP_TRY(hipGetLastError());
+            tc = tv;
+        }
+        if (norm) {   // X holds the raw hidden states: normalise the chunk's rows
             ScopedKernelTimer timer(FLCE_KIND_OTHER, s);
             hipLaunchKernelGGL((rmsnorm_fwd_kernel<T>), dim3((unsigned)rows), dim3(RN_THREADS), 0, s,
-                               X + r0 * H, norm->gamma, norm->eps, (int)H, norm->Y, norm->rstd);
+                               Xin, norm->gamma, norm->eps, (int)H, Xg, norm->rstd, row_map, n_live);
             HIP_TRY(hipGetLastError());
-            Xc = norm->Y;
+            Xc = Xg;
+        } else if (p.compact) {
+            ScopedKernelTimer timer(FLCE_KIND_OTHER, s);
+            hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)rows), dim3(256), 0, s,
+                               reinterpret_cast<const u32x4*>(X), idx, n_live, (int)(H / VEC),
+                               reinterpret_cast<u32x4*>(Xg));
+            HIP_TRY(hipGetLastError());
+            Xc = Xg;
         }
 
         // logits of the chunk: Z = X_c W^T
         if (BF16 && p.fast_logits) {
             if constexpr (BF16)
                 FLCE_TRY((launch_gemm_fast<bf16_t, void, false, false>(
-                    FLCE_KIND_LOGITS_GEMM, Xc, H, W, H, Z, p.ldz, nullptr, 0, rows, V, H, s)));
+                    FLCE_KIND_LOGITS_GEMM, Xc, H, W, H, Z, p.ldz, nullptr, 0, rows, V, H, s, 1, 0,
+                    n_live, 0)));
         } else {
             FLCE_TRY((launch_gemm_generic<T, T>(FLCE_KIND_LOGITS_GEMM, Xc, H, W, H, Z, p.ldz, rows, V, H,
                                                 false, s)));
         }
 
         // loss and in-place dlogits
-        FLCE_TRY(launch_ce_rows<T>(Z, p.ldz, targets + r0, rows, V, (int)(p.ldz - V), ignore_index, hdr,
-                                   row_loss, s));
+        FLCE_TRY(launch_ce_rows<T>(Z, p.ldz, tc, rows, V, (int)(p.ldz - V), ignore_index, hdr,
+                                   row_loss, s, n_live));
 
         // dX_c (+)= G W
         if (want_dx) {
-            T* dXc = norm ? norm->dY : dX + r0 * H;
+            // where the product writes: straight into dX, or into the chunk buffer when the rows
+            // still have to be scattered back or to pass through the RMSNorm backward
+            const bool staged = p.compact || norm;
+            T* dXc = staged ? dXg : dX + r0 * H;
+            const bool add_in_gemm = dx_add && !staged;
             if (BF16 && p.fast_dx) {
                 if constexpr (BF16) {
                     if (p.dx_ksplit > 1) {
@@ -270,53 +312,68 @@ int run_head(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t
                         float* part = reinterpret_cast<float*>(ws + p.off_dxpart);
                         FLCE_TRY((launch_gemm_fast<float, void, false, true>(
                             FLCE_KIND_DX_GEMM, Z, p.ldz, W, H, part, H, nullptr, 0, rows, H, V, s,
-                            p.dx_ksplit, p.C * H)));
+                            p.dx_ksplit, p.C * H, n_live, 0)));
                         ScopedKernelTimer timer(FLCE_KIND_DX_GEMM, s);
-                        if (dx_add)
+                        if (add_in_gemm)
                             hipLaunchKernelGGL((splitk_reduce_kernel<bf16_t, true>), dim3(1024), dim3(256),
                                                0, s, part, p.C * H, p.dx_ksplit, dXc, rows * H);
                         else
                             hipLaunchKernelGGL((splitk_reduce_kernel<bf16_t, false>), dim3(1024), dim3(256),
                                                0, s, part, p.C * H, p.dx_ksplit, dXc, rows * H);
                         HIP_TRY(hipGetLastError());
-                    } else if (dx_add) {
+                    } else if (add_in_gemm) {
                         FLCE_TRY((launch_gemm_fast<bf16_t, bf16_t, false, true>(
                             FLCE_KIND_DX_GEMM, Z, p.ldz, W, H, dXc, H, dXc, H, rows, H, V, s)));
                     } else {
                         FLCE_TRY((launch_gemm_fast<bf16_t, void, false, true>(
-                            FLCE_KIND_DX_GEMM, Z, p.ldz, W, H, dXc, H, nullptr, 0, rows, H, V, s)));
+                            FLCE_KIND_DX_GEMM, Z, p.ldz, W, H, dXc, H, nullptr, 0, rows, H, V, s, 1, 0,
+                            n_live, 0)));
                     }
                 }
             } else {
                 FLCE_TRY((launch_gemm_generic<T, T>(FLCE_KIND_DX_GEMM, Z, p.ldz, WT, p.ldz, dXc, H, rows,
-                                                    H, V, dx_add, s)));
+                                                    H, V, add_in_gemm, s)));
             }
             if (norm) {
                 ScopedKernelTimer timer(FLCE_KIND_OTHER, s);
-                hipLaunchKernelGGL((rmsnorm_bwd_kernel<T>), dim3(RN_SLOTS), dim3(RN_THREADS), 0, s,
-                                   X + r0 * H, norm->gamma, norm->rstd, norm->dY, (int)rows, (int)H,
-                                   norm->dh + r0 * H, norm->partial);
+                hipLaunchKernelGGL((rmsnorm_bwd_kernel<T>), dim3(RN_SLOTS), dim3(RN_THREADS), 0, s, Xin,
+                                   norm->gamma, norm->rstd, dXg, (int)rows, (int)H,
+                                   p.compact ? norm->dh : norm->dh + r0 * H, norm->partial, row_map,
+                                   n_live);
+                HIP_TRY(hipGetLastError());
+            } else if (p.compact) {
+                ScopedKernelTimer timer(FLCE_KIND_OTHER, s);
+                if (dx_add)
+                    hipLaunchKernelGGL((scatter_rows_kernel<T, true>), dim3((unsigned)rows), dim3(256), 0,
+                                       s, static_cast<const T*>(dXg), idx, n_live, (int)H, dX);
+                else
+                    hipLaunchKernelGGL((scatter_rows_kernel<T, false>), dim3((unsigned)rows), dim3(256), 0,
+                                       s, static_cast<const T*>(dXg), idx, n_live, (int)H, dX);
                 HIP_TRY(hipGetLastError());
             }
         }
 
-        // dW (+)= G^T X_c
+        // dW (+)= G^T X_c   (K = the chunk's rows; in a compacted chunk K = *n_live)
         if (want_dw) {
             const bool fast = BF16 && (last ? p.fast_dw_last : p.fast_dw_full);
             if (fast) {
                 if constexpr (BF16) {
                     if (p.nchunks == 1) {
                         FLCE_TRY((launch_gemm_fast<bf16_t, void, true, true>(
-                            FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dW, H, nullptr, 0, V, H, rows, s)));
+                            FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dW, H, nullptr, 0, V, H, rows, s, 1, 0,
+                            n_live, 1)));
                     } else if (c == 0) {
                         FLCE_TRY((launch_gemm_fast<float, void, true, true>(
-                            FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dWacc, H, nullptr, 0, V, H, rows, s)));
+                            FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dWacc, H, nullptr, 0, V, H, rows, s, 1, 0,
+                            n_live, 1)));
                     } else if (!last) {
                         FLCE_TRY((launch_gemm_fast<float, float, true, true>(
-                            FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dWacc, H, dWacc, H, V, H, rows, s)));
+                            FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dWacc, H, dWacc, H, V, H, rows, s, 1, 0,
+                            n_live, 1)));
                     } else {   // last chunk: add the fp32 partial sums and write dW in bf16
                         FLCE_TRY((launch_gemm_fast<bf16_t, float, true, true>(
-                            FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dW, H, dWacc, H, V, H, rows, s)));
+                            FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dW, H, dWacc, H, V, H, rows, s, 1, 0,
+                            n_live, 1)));
                     }
                 }
             } else {
@@ -373,9 +430,9 @@ int check_dims(int64_t BT, int64_t H, int64_t V, int dtype) {
 }
 
 struct NormLayout {
-    size_t off_y, off_dy, off_rstd, off_partial, total;
+    size_t off_rstd, off_partial, total;
 };
-NormLayout norm_layout(const Plan& p, int64_t H, int dtype) {
+NormLayout norm_layout(const Plan& p, int64_t H) {
     NormLayout l{};
     size_t off = p.total;
     auto take = [&](size_t bytes) {
@@ -383,8 +440,6 @@ NormLayout norm_layout(const Plan& p, int64_t H, int dtype) {
         off += (bytes + 255) / 256 * 256;
         return at;
     };
-    l.off_y = take((size_t)p.C * H * elem_size(dtype));
-    l.off_dy = take((size_t)p.C * H * elem_size(dtype));
     l.off_rstd = take((size_t)p.C * sizeof(float));
     l.off_partial = take((size_t)RN_SLOTS * H * sizeof(float));
     l.total = off;
@@ -397,9 +452,8 @@ int run_rmsnorm_head(const T* h, const T* gamma, float eps, const T* W, const in
                      T* dgamma, T* dW, unsigned flags, const Plan& p, const NormLayout& l, char* ws,
                      hipStream_t s) {
     const bool want_dx = !(flags & FLCE_SKIP_DX);
-    NormCtx<T> n{gamma, eps, reinterpret_cast<T*>(ws + l.off_y), reinterpret_cast<T*>(ws + l.off_dy),
-                 reinterpret_cast<float*>(ws + l.off_rstd), reinterpret_cast<float*>(ws + l.off_partial),
-                 dh};
+    NormCtx<T> n{gamma, eps, reinterpret_cast<float*>(ws + l.off_rstd),
+                 reinterpret_cast<float*>(ws + l.off_partial), dh};
     DeviceHeader* hdr = reinterpret_cast<DeviceHeader*>(ws + p.off_hdr);
     if (want_dx) {
         hipLaunchKernelGGL(fill_zero_kernel, dim3(256), dim3(256), 0, s, n.partial,
@@ -448,7 +502,7 @@ int flce_multihead_fwd_bwd(const void* X, const void* const* W, const int64_t* c
     }
     if (ignore_index >= 0 && ignore_index < V) return FLCE_ERR_ARG;   // would shadow a class
 
-    const Plan p = make_plan(BT, H, V, dtype, g_budget);
+    const Plan p = make_plan(BT, H, V, dtype, g_budget, false, g_compact);
     char* ws = nullptr;
     FLCE_TRY(acquire_workspace(p.total, &ws));
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -477,8 +531,8 @@ int flce_rmsnorm_fwd_bwd(const void* h, const void* gamma, float eps, const void
     if (ignore_index >= 0 && ignore_index < V) return FLCE_ERR_ARG;
     if (!(eps >= 0.0f) || eps - eps != 0.0f) return FLCE_ERR_ARG;   // negative, NaN or infinite
 
-    const Plan p = make_plan(BT, H, V, dtype, g_budget);
-    const NormLayout l = norm_layout(p, H, dtype);
+    const Plan p = make_plan(BT, H, V, dtype, g_budget, false, g_compact);
+    const NormLayout l = norm_layout(p, H);
     char* ws = nullptr;
     FLCE_TRY(acquire_workspace(l.total, &ws));
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -497,7 +551,7 @@ int flce_rmsnorm_fwd_bwd(const void* h, const void* gamma, float eps, const void
 
 size_t flce_rmsnorm_workspace_bytes(int64_t BT, int64_t H, int64_t V, int dtype) {
     if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
-    return norm_layout(make_plan(BT, H, V, dtype, g_budget), H, dtype).total;
+    return norm_layout(make_plan(BT, H, V, dtype, g_budget, false, g_compact), H).total;
 }
 
 int flce_fwd_bwd_ex(const void* X, const void* W, const int64_t* targets, int64_t BT, int64_t H,
@@ -552,12 +606,12 @@ int flce_cross_entropy_inplace(void* Z, const int64_t* targets, int64_t BT, int6
 
 size_t flce_workspace_bytes(int64_t BT, int64_t H, int64_t V, int dtype) {
     if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
-    return make_plan(BT, H, V, dtype, g_budget).total;
+    return make_plan(BT, H, V, dtype, g_budget, false, g_compact).total;
 }
 
 size_t flce_workspace_bytes_max(int64_t H, int64_t V, int dtype) {
     if (check_dims(1, H, V, dtype) != FLCE_OK) return 0;
-    return make_plan(0, H, V, dtype, g_budget, true).total;
+    return make_plan(0, H, V, dtype, g_budget, true, g_compact).total;
 }
 
 int flce_set_workspace(void* ws, size_t bytes) {
@@ -595,19 +649,27 @@ int flce_set_logits_budget_bytes(size_t bytes) {
 
 size_t flce_get_logits_budget_bytes(void) { return g_budget; }
 
+int flce_set_row_compaction(int on) {
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_compact = (on != 0);
+    return FLCE_OK;
+}
+
+int flce_get_row_compaction(void) { return g_compact ? 1 : 0; }
+
 int64_t flce_chunk_rows(int64_t BT, int64_t H, int64_t V, int dtype) {
     if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
-    return make_plan(BT, H, V, dtype, g_budget).C;
+    return make_plan(BT, H, V, dtype, g_budget, false, g_compact).C;
 }
 
 int64_t flce_num_chunks(int64_t BT, int64_t H, int64_t V, int dtype) {
     if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
-    return make_plan(BT, H, V, dtype, g_budget).nchunks;
+    return make_plan(BT, H, V, dtype, g_budget, false, g_compact).nchunks;
 }
 
 int flce_dx_k_ranges(int64_t BT, int64_t H, int64_t V, int dtype) {
     if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
-    return make_plan(BT, H, V, dtype, g_budget).dx_ksplit;
+    return make_plan(BT, H, V, dtype, g_budget, false, g_compact).dx_ksplit;
 }
 
 int64_t flce_paper_chunk_rows(int64_t BT, int64_t H, int64_t V) {

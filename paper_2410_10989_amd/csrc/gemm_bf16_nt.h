@@ -82,6 +82,12 @@ struct FGArgs {
     int tiles_m, tiles_n;
     int ksplit;            // K is cut into this many ranges (>= 1), one workgroup per tile and range
     int64_t split_stride;  // elements between the partial results of consecutive K ranges in C
+    // Row count known on the device only (a chunk's number of non-ignored rows): when
+    // dyn_rows is not null, min(*dyn_rows, static size) replaces M
+    // (dyn_is_k = 0) or K (dyn_is_k = 1, column-form operands only).  The grid is
+    // launched for the static size; workgroups of tiles past the dynamic M return at once.
+    const int* dyn_rows;
+    int dyn_is_k;
 };
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -267,6 +273,11 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
     const int wm = wave >> 1, wn = wave & 1;
 
     // ---- workgroup id -> (K range, tile) (XCD aware, grouped order) ----
+    int M = a.M, K = a.K;
+    if (a.dyn_rows) {
+        const int r = *a.dyn_rows;   // uniform: a scalar load
+        if (a.dyn_is_k) K = min(K, r); else M = min(M, r);
+    }
     const int tiles = a.tiles_m * a.tiles_n;
     const int per_xcd = (int)gridDim.x / FG_XCDS;
     const int seq_all = ((int)blockIdx.x % FG_XCDS) * per_xcd + (int)blockIdx.x / FG_XCDS;
@@ -280,11 +291,12 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
     const int rem = seq - grp * group_size;
     const int pm = first_m + rem % gm, pn = rem / gm;
     const int m0 = pm * FG_BM, n0 = pn * FG_BN;
+    if (m0 >= M) return;
 
     FgOperand<A_KM> opa;
     FgOperand<B_KM> opb;
-    opa.init(a.A, a.lda, m0, a.M, a.K, tid, wm);
-    opb.init(a.B, a.ldb, n0, a.N, a.K, tid, wn);
+    opa.init(a.A, a.lda, m0, M, K, tid, wm);
+    opb.init(a.B, a.ldb, n0, a.N, K, tid, wn);
     const int uwave = __builtin_amdgcn_readfirstlane(wave);
 
     const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
@@ -384,7 +396,7 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
     };
 
     // K steps [k_begin, k_begin + nk) belong to this workgroup
-    const int steps_all = (a.K + FG_BK - 1) / FG_BK;
+    const int steps_all = (K + FG_BK - 1) / FG_BK;
     const int k_begin = (int)((int64_t)steps_all * split / a.ksplit);
     const int nk = (int)((int64_t)steps_all * (split + 1) / a.ksplit) - k_begin;
     opa.start_at(k_begin);
@@ -431,7 +443,7 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
     // arithmetic is needed. ----
     constexpr int ES = (int)sizeof(OutT);
     const int frow = lane & 31, fhalf = lane >> 5;
-    const int rows_c = min(FG_BM, a.M - m0);
+    const int rows_c = min(FG_BM, M - m0);
     const int ldc = (int)a.ldc, ldcin = (int)a.ldcin;
     const __amdgpu_buffer_rsrc_t rsrc_c =
         fg_make_rsrc(static_cast<OutT*>(a.C) + (int64_t)split * a.split_stride + (int64_t)m0 * a.ldc,

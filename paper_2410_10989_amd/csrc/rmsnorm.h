@@ -28,15 +28,21 @@ __device__ __forceinline__ float rn_block_sum(float v, float* red) {
     return (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-// One workgroup per row: y = x / rms(x) * gamma, rstd[row] = 1 / rms(x).
+// One workgroup per output row: y = x / rms(x) * gamma, rstd[row] = 1 / rms(x).
+// With idx / live (a compacted chunk) output row i reads input row idx[i], and
+// workgroups past the chunk's *live rows return.
 template <typename T>
 __global__ __launch_bounds__(RN_THREADS) void rmsnorm_fwd_kernel(const T* __restrict__ x,
                                                                  const T* __restrict__ gamma,
                                                                  float eps, int n,
                                                                  T* __restrict__ y,
-                                                                 float* __restrict__ rstd) {
+                                                                 float* __restrict__ rstd,
+                                                                 const int* __restrict__ idx,
+                                                                 const int* __restrict__ live) {
     __shared__ float red[RN_THREADS / WAVE];
-    const int64_t base = (int64_t)blockIdx.x * n;
+    if (live && (int)blockIdx.x >= *live) return;
+    const int64_t base = (int64_t)(idx ? idx[blockIdx.x] : (int)blockIdx.x) * n;
+    const int64_t obase = (int64_t)blockIdx.x * n;
     float ss = 0.f;
     for (int j = threadIdx.x; j < n; j += RN_THREADS) {
         const float v = to_f32(x[base + j]);
@@ -46,28 +52,33 @@ __global__ __launch_bounds__(RN_THREADS) void rmsnorm_fwd_kernel(const T* __rest
     const float r = 1.0f / sqrtf(ss / (float)n + eps);
     if (threadIdx.x == 0) rstd[blockIdx.x] = r;
     for (int j = threadIdx.x; j < n; j += RN_THREADS)
-        y[base + j] = from_f32<T>(to_f32(x[base + j]) * r * to_f32(gamma[j]));
+        y[obase + j] = from_f32<T>(to_f32(x[base + j]) * r * to_f32(gamma[j]));
 }
 
 // Workgroup p: rows p, p + RN_SLOTS, ... of this chunk.  dx is written; the
 // workgroup's own row of `partial` accumulates dy * xhat (column j always by the
 // same thread, so there is no race and the order of additions is fixed).
+// With idx / live (a compacted chunk) dy and rstd are indexed by the chunk's row i, x and
+// dx by row idx[i], and only *live rows exist.
 template <typename T>
 __global__ __launch_bounds__(RN_THREADS) void rmsnorm_bwd_kernel(
     const T* __restrict__ x, const T* __restrict__ gamma, const float* __restrict__ rstd,
-    const T* __restrict__ dy, int rows, int n, T* __restrict__ dx, float* __restrict__ partial) {
+    const T* __restrict__ dy, int rows, int n, T* __restrict__ dx, float* __restrict__ partial,
+    const int* __restrict__ idx, const int* __restrict__ live) {
     __shared__ float red[RN_THREADS / WAVE];
     float* mine = partial + (int64_t)blockIdx.x * n;
+    if (live) rows = min(rows, *live);
     for (int row = blockIdx.x; row < rows; row += RN_SLOTS) {
-        const int64_t base = (int64_t)row * n;
+        const int64_t base = (int64_t)(idx ? idx[row] : row) * n;
+        const int64_t cbase = (int64_t)row * n;
         const float r = rstd[row];
         float dot = 0.f;
         for (int j = threadIdx.x; j < n; j += RN_THREADS)
-            dot += (to_f32(x[base + j]) * r) * (to_f32(dy[base + j]) * to_f32(gamma[j]));
+            dot += (to_f32(x[base + j]) * r) * (to_f32(dy[cbase + j]) * to_f32(gamma[j]));
         dot = rn_block_sum(dot, red) / (float)n;
         for (int j = threadIdx.x; j < n; j += RN_THREADS) {
             const float xh = to_f32(x[base + j]) * r;
-            const float d = to_f32(dy[base + j]);
+            const float d = to_f32(dy[cbase + j]);
             dx[base + j] = from_f32<T>(r * (d * to_f32(gamma[j]) - dot * xh));
             mine[j] += d * xh;
         }

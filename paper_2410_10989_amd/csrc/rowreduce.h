@@ -159,10 +159,15 @@ __device__ __forceinline__ float row_lse(MaxSum a, const T* z, int64_t t, int ro
 template <typename T, bool VEC16>
 __global__ __launch_bounds__(RR_THREADS) void ce_rows_inplace_kernel(
     T* __restrict__ Z, int64_t ldz, const int64_t* __restrict__ targets, int V, int zero_pad,
-    int64_t ignore_index, const DeviceHeader* __restrict__ hdr, float* __restrict__ row_loss) {
+    int64_t ignore_index, const DeviceHeader* __restrict__ hdr, float* __restrict__ row_loss,
+    const int* __restrict__ live) {
     constexpr int VEC = RowVec<T>::N;
     const int row = blockIdx.x;
     const int tid = threadIdx.x;
+    if (live && row >= *live) {   // past the chunk's live rows (uniform per workgroup)
+        if (tid == 0) row_loss[row] = 0.f;
+        return;
+    }
     T* z = Z + (int64_t)row * ldz;
     const int64_t t = targets[row];
     const bool valid = (t != ignore_index);
@@ -217,10 +222,15 @@ constexpr int RC_NV = 16;
 template <typename T>
 __global__ __launch_bounds__(RC_THREADS) void ce_rows_cached_kernel(
     T* __restrict__ Z, int64_t ldz, const int64_t* __restrict__ targets, int V, int zero_pad,
-    int64_t ignore_index, const DeviceHeader* __restrict__ hdr, float* __restrict__ row_loss) {
+    int64_t ignore_index, const DeviceHeader* __restrict__ hdr, float* __restrict__ row_loss,
+    const int* __restrict__ live) {
     constexpr int VEC = RowVec<T>::N;
     const int row = blockIdx.x;
     const int tid = threadIdx.x;
+    if (live && row >= *live) {   // past the chunk's live rows (uniform per workgroup)
+        if (tid == 0) row_loss[row] = 0.f;
+        return;
+    }
     T* z = Z + (int64_t)row * ldz;
     const int64_t t = targets[row];
     const bool valid = (t != ignore_index);

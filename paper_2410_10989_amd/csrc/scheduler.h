@@ -29,9 +29,13 @@ struct Plan {
     // logits chunk; the others need transposed copies and the guarded kernel
     bool fast_logits = false, fast_dx = false, fast_dw_full = false, fast_dw_last = false;
     int dx_ksplit = 1;     // K ranges of the dX product (K = V), > 1 when C x H has few tiles
+    // every product of every chunk runs on the tuned kernel: chunks are compacted, i.e.
+    // rows with an ignored target are left out of the products (see compact.h)
+    bool compact = false;
     // byte offsets into the workspace
     size_t off_hdr = 0, off_row_loss = 0, off_z = 0, off_gt = 0, off_wt = 0, off_xt = 0,
-           off_dwacc = 0, off_dxpart = 0, total = 0;
+           off_dwacc = 0, off_dxpart = 0, off_xg = 0, off_dxg = 0, off_idx = 0, off_tv = 0,
+           off_dyn = 0, total = 0;
 };
 
 // How many K ranges to cut a product with `tiles` output tiles and `ksteps` K steps
@@ -68,7 +72,7 @@ inline bool fits_row_form(int64_t ld, int64_t) { return 256 * ld * 2 + 128 < ((i
 inline bool fits_col_form(int64_t ld, int64_t) { return 64 * ld * 2 + 512 < ((int64_t)1 << 30); }
 
 inline Plan make_plan(int64_t BT, int64_t H, int64_t V, int dtype, size_t budget_bytes,
-                      bool worst_case_bt = false) {
+                      bool worst_case_bt = false, bool allow_compact = true) {
     Plan p;
     const size_t es = elem_size(dtype);
     p.ldz = round_up(V, 64);
@@ -111,6 +115,7 @@ inline Plan make_plan(int64_t BT, int64_t H, int64_t V, int dtype, size_t budget
         p.dx_ksplit = choose_ksplit(((rows + 255) / 256) * ((H + 255) / 256), (V + 63) / 64,
                                     max_dx_ranges(budget_bytes, round_up(rows, 256), H));
     }
+    p.compact = allow_compact && p.fast_logits && p.fast_dx && p.fast_dw_full && p.fast_dw_last;
     const bool need_wt = !p.fast_dx;
     const bool need_gt = !(p.fast_dw_full && p.fast_dw_last);
 
@@ -137,6 +142,13 @@ inline Plan make_plan(int64_t BT, int64_t H, int64_t V, int dtype, size_t budget
         }
     }
     p.off_dxpart = take(dxpart);
+    // a chunk of gathered input rows and of their gradient (also the normalised rows and
+    // their gradient when an RMSNorm runs in front), index maps of the compaction
+    p.off_xg = take((size_t)p.C * H * es);
+    p.off_dxg = take((size_t)p.C * H * es);
+    p.off_idx = take(p.compact ? (size_t)p.C * sizeof(int32_t) : 0);
+    p.off_tv = take(p.compact ? (size_t)p.C * sizeof(int64_t) : 0);
+    p.off_dyn = take(256);
     p.total = off;
     return p;
 }

@@ -222,3 +222,67 @@ def test_call_can_be_captured_in_a_graph_and_replayed():
             assert torch.equal(got[2].view(torch.int16), e_dW.view(torch.int16))
     finally:
         flce.flce_set_logits_budget_bytes(old)
+
+
+# ---- row compaction: rows with an ignored target are left out of the products ----
+
+def _with_budget_rows(rows_per_chunk, V, fn):
+    import paper_2410_10989_amd as flce
+    old = flce.flce_get_logits_budget_bytes()
+    try:
+        flce.flce_set_logits_budget_bytes(rows_per_chunk * ((V + 63) // 64 * 64) * 2)
+        return fn()
+    finally:
+        flce.flce_set_logits_budget_bytes(old)
+
+
+@pytest.mark.parametrize("frac", [0.9, 0.5, 0.26])
+def test_mostly_ignored_rows_leave_trailing_chunks_empty(frac):
+    # 4 chunks of 256 rows are launched; the valid rows fill only the first one(s), the others run
+    # with zero live rows (their dW launches only pass the partial sums on)
+    import paper_2410_10989_amd as flce
+    w = workloads.make(1024, 128, 1000, "bf16", ignore=("iid", frac), seed=900 + int(frac * 100),
+                       name="sparse_targets")
+    assert flce.flce_get_row_compaction()
+
+    def run():
+        assert flce.flce_num_chunks(w.BT, w.H, w.V, flce.FLCE_BF16) == 4
+        return check_full(w)
+    _with_budget_rows(256, w.V, run)
+
+
+def test_valid_rows_exactly_fill_the_chunks():
+    import paper_2410_10989_amd as flce
+    w = workloads.make(768, 64, 512, "bf16", seed=5, name="exact_fill")
+    w.targets[np.arange(768) % 3 == 2] = w.ignore_index      # 512 valid rows = 2 chunks of 256
+    assert w.n_valid == 512
+    _with_budget_rows(256, w.V, lambda: check_full(w))
+
+
+def test_all_rows_ignored_with_several_chunks():
+    w = workloads.make(700, 64, 384, "bf16", seed=6, name="all_ignored_chunked")
+    w.targets[:] = w.ignore_index
+
+    def run():
+        loss, dX, dW = run_gpu(w)
+        assert loss == 0.0 and (to_host(dX) == 0).all() and (to_host(dW) == 0).all()
+    _with_budget_rows(256, w.V, run)
+
+
+def test_compaction_on_and_off_agree():
+    # dX rows are computed by the same arithmetic either way (bitwise equal); dW sums the same
+    # non-zero terms in other groups of K, the loss adds the same row losses in another order
+    import paper_2410_10989_amd as flce
+    w = workloads.make(1300, 256, 2048, "bf16", ignore=("pad", 100, 60), seed=77, name="on_off")
+    on = run_gpu(w)
+    try:
+        flce.flce_set_row_compaction(False)
+        off = run_gpu(w)
+    finally:
+        flce.flce_set_row_compaction(True)
+    assert abs(on[0] - off[0]) <= 1e-6 * abs(off[0])
+    assert torch.equal(on[1].view(torch.int16), off[1].view(torch.int16))
+    err = (on[2].float() - off[2].float()).abs().max().item()
+    assert err <= 2.0 ** -7 * off[2].float().abs().max().item()
+    ref = oracle.flce(w.X, w.W, w.targets, w.ignore_index)
+    assert_close("dW (compaction off)", to_host(off[2]), ref.dW, TOL["bf16"][1])
