@@ -255,6 +255,8 @@ def main():
                      "unit": "TFLOP/s", "frac": achieved / peak,
                      "avg_launch_ms": dom_avg_ms, "launches": dom_n,
                      "flops_per_launch": flops_per_launch,
+                     # the same with the nominal count (every row of the batch, ignored or not)
+                     "achieved_nominal": achieved * (w.BT * nh) / rows_projected,
                      "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH
                      if args.config == 3 and dom == "logits_gemm" and not args.budget_mib else None},
     }
