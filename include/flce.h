@@ -116,7 +116,9 @@ FLCE_API int flce_fwd_bwd_ex(const void* X, const void* W, const int64_t* target
  * None of the heads' logits is stored whole: the heads run one after the other
  * through the same chunk loop and the same workspace, so peak extra memory is
  * that of a single head.  dX is summed in its storage type: head 0 writes it,
- * every later head adds its fp32 product to the stored value and rounds once.
+ * every later head's rows are added to the stored rows in fp32 and rounded (with
+ * row compaction, see flce_set_row_compaction, the head's rows are themselves
+ * rounded once before that addition).
  *
  *   W, targets, dW   HOST arrays of n_heads DEVICE pointers ([V x H] dtype,
  *                    [BT] int64, [V x H] dtype); read before the call returns.
