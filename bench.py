@@ -237,7 +237,7 @@ def main():
         "config": {"workload": f"config{args.config}:{w.name}", "BT": w.BT, "H": w.H, "V": w.V,
                    "ignore_frac": round(1 - w.n_valid / w.BT, 4), "chunk_rows":
                    flce.flce_chunk_rows(w.BT, w.H, w.V, code), "chunks": nchunks,
-                   "logits_budget_mib": flce.flce_get_logits_budget_bytes() >> 20},
+                   "logits_budget_mib": (flce.flce_get_logits_budget_bytes() >> 20) or "auto"},
         "heads": nh,
         "tflops_over_6BTHV": tflops,   # nominal: over 6*BT*H*V per head (4*BT*H*V without dX)
         "mfma_util_frac_of_peak": tflops / peak,

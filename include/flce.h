@@ -187,8 +187,11 @@ FLCE_API int flce_set_workspace(void* ws, size_t bytes);
 FLCE_API int flce_release_workspace(void);
 
 /* Chunk scheduler (paper section 3.2, FLCE paragraph: chunked logits bound the
- * memory).  The logits chunk [C x V] is sized to fit this many bytes; default
- * 1 GiB.  Returns FLCE_ERR_ARG for 0. */
+ * memory).  The logits chunk [C x V] is sized to fit this many bytes.  0 (the
+ * default) selects the automatic rule: 1 GiB, but at least 4096 rows of logits
+ * (each chunk re-reads W twice and read-modify-writes the fp32 dW partial sums,
+ * which only pays off over a few thousand rows).  The getter returns the setting
+ * (0 = automatic). */
 FLCE_API int flce_set_logits_budget_bytes(size_t bytes);
 FLCE_API size_t flce_get_logits_budget_bytes(void);
 

@@ -22,6 +22,8 @@ namespace {
 constexpr int MAX_DEVICES = 64;
 constexpr int64_t MAX_DIM = (int64_t)1 << 30;      // per-dimension limit, keeps int tile math safe
 constexpr int64_t CE_ROWS_PER_LAUNCH = 65536;
+constexpr size_t AUTO_BUDGET_BYTES = (size_t)1 << 30;
+constexpr int64_t AUTO_BUDGET_MIN_ROWS = 4096;
 
 struct DeviceWorkspace {
     void* lent = nullptr;
@@ -32,8 +34,18 @@ struct DeviceWorkspace {
 
 std::mutex g_mutex;
 DeviceWorkspace g_ws[MAX_DEVICES];
-size_t g_budget = (size_t)1 << 30;
+size_t g_budget = 0;   // 0 = the automatic rule of effective_budget()
 bool g_compact = true;
+
+// The byte budget of the logits chunk: what the caller set, or by default 1 GiB but at
+// least 4096 rows of logits.  Every chunk costs one more pass over W and an fp32
+// read-modify-write of the dW partial sums (16 V H bytes) whatever its row count, which
+// is about 433 / C of the chunk's product time on this chip: 10 % at 4096 rows.
+size_t effective_budget(int64_t V, int dtype) {
+    if (g_budget) return g_budget;
+    const size_t rows_bytes = (size_t)AUTO_BUDGET_MIN_ROWS * (size_t)round_up(V, 64) * elem_size(dtype);
+    return rows_bytes > AUTO_BUDGET_BYTES ? rows_bytes : AUTO_BUDGET_BYTES;
+}
 
 // ---- optional per-kernel timing (benchmarks only) ----
 struct TimingRecord {
@@ -502,7 +514,7 @@ int flce_multihead_fwd_bwd(const void* X, const void* const* W, const int64_t* c
     }
     if (ignore_index >= 0 && ignore_index < V) return FLCE_ERR_ARG;   // would shadow a class
 
-    const Plan p = make_plan(BT, H, V, dtype, g_budget, false, g_compact);
+    const Plan p = make_plan(BT, H, V, dtype, effective_budget(V, dtype), false, g_compact);
     char* ws = nullptr;
     FLCE_TRY(acquire_workspace(p.total, &ws));
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -531,7 +543,7 @@ int flce_rmsnorm_fwd_bwd(const void* h, const void* gamma, float eps, const void
     if (ignore_index >= 0 && ignore_index < V) return FLCE_ERR_ARG;
     if (!(eps >= 0.0f) || eps - eps != 0.0f) return FLCE_ERR_ARG;   // negative, NaN or infinite
 
-    const Plan p = make_plan(BT, H, V, dtype, g_budget, false, g_compact);
+    const Plan p = make_plan(BT, H, V, dtype, effective_budget(V, dtype), false, g_compact);
     const NormLayout l = norm_layout(p, H);
     char* ws = nullptr;
     FLCE_TRY(acquire_workspace(l.total, &ws));
@@ -551,7 +563,7 @@ int flce_rmsnorm_fwd_bwd(const void* h, const void* gamma, float eps, const void
 
 size_t flce_rmsnorm_workspace_bytes(int64_t BT, int64_t H, int64_t V, int dtype) {
     if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
-    return norm_layout(make_plan(BT, H, V, dtype, g_budget, false, g_compact), H).total;
+    return norm_layout(make_plan(BT, H, V, dtype, effective_budget(V, dtype), false, g_compact), H).total;
 }
 
 int flce_fwd_bwd_ex(const void* X, const void* W, const int64_t* targets, int64_t BT, int64_t H,
@@ -606,12 +618,12 @@ int flce_cross_entropy_inplace(void* Z, const int64_t* targets, int64_t BT, int6
 
 size_t flce_workspace_bytes(int64_t BT, int64_t H, int64_t V, int dtype) {
     if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
-    return make_plan(BT, H, V, dtype, g_budget, false, g_compact).total;
+    return make_plan(BT, H, V, dtype, effective_budget(V, dtype), false, g_compact).total;
 }
 
 size_t flce_workspace_bytes_max(int64_t H, int64_t V, int dtype) {
     if (check_dims(1, H, V, dtype) != FLCE_OK) return 0;
-    return make_plan(0, H, V, dtype, g_budget, true, g_compact).total;
+    return make_plan(0, H, V, dtype, effective_budget(V, dtype), true, g_compact).total;
 }
 
 int flce_set_workspace(void* ws, size_t bytes) {
@@ -641,7 +653,6 @@ int flce_release_workspace(void) {
 }
 
 int flce_set_logits_budget_bytes(size_t bytes) {
-    if (bytes == 0) return FLCE_ERR_ARG;
     std::lock_guard<std::mutex> lock(g_mutex);
     g_budget = bytes;
     return FLCE_OK;
@@ -659,17 +670,17 @@ int flce_get_row_compaction(void) { return g_compact ? 1 : 0; }
 
 int64_t flce_chunk_rows(int64_t BT, int64_t H, int64_t V, int dtype) {
     if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
-    return make_plan(BT, H, V, dtype, g_budget, false, g_compact).C;
+    return make_plan(BT, H, V, dtype, effective_budget(V, dtype), false, g_compact).C;
 }
 
 int64_t flce_num_chunks(int64_t BT, int64_t H, int64_t V, int dtype) {
     if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
-    return make_plan(BT, H, V, dtype, g_budget, false, g_compact).nchunks;
+    return make_plan(BT, H, V, dtype, effective_budget(V, dtype), false, g_compact).nchunks;
 }
 
 int flce_dx_k_ranges(int64_t BT, int64_t H, int64_t V, int dtype) {
     if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
-    return make_plan(BT, H, V, dtype, g_budget, false, g_compact).dx_ksplit;
+    return make_plan(BT, H, V, dtype, effective_budget(V, dtype), false, g_compact).dx_ksplit;
 }
 
 int64_t flce_paper_chunk_rows(int64_t BT, int64_t H, int64_t V) {

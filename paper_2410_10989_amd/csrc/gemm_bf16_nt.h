@@ -278,20 +278,25 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
         const int r = *a.dyn_rows;   // uniform: a scalar load
         if (a.dyn_is_k) K = min(K, r); else M = min(M, r);
     }
-    const int tiles = a.tiles_m * a.tiles_n;
-    const int per_xcd = (int)gridDim.x / FG_XCDS;
-    const int seq_all = ((int)blockIdx.x % FG_XCDS) * per_xcd + (int)blockIdx.x / FG_XCDS;
-    if (seq_all >= tiles * a.ksplit) return;
+    // The tile sequence covers the live rows only (a dynamic M can be smaller than the M the
+    // grid was sized for): the live tiles are dealt evenly to the XCDs, and the workgroups
+    // that are left over have the highest ids, are dispatched last and return at once.
+    const int tiles_m = (M + FG_BM - 1) / FG_BM;
+    const int tiles = tiles_m * a.tiles_n;
+    const int total = tiles * a.ksplit;
+    const int per_xcd = (total + FG_XCDS - 1) / FG_XCDS;
+    const int in_xcd = (int)blockIdx.x / FG_XCDS;
+    const int seq_all = ((int)blockIdx.x % FG_XCDS) * per_xcd + in_xcd;
+    if (in_xcd >= per_xcd || seq_all >= total) return;
     const int split = seq_all / tiles;
     const int seq = seq_all - split * tiles;
     const int group_size = FG_GROUP_M * a.tiles_n;
     const int grp = seq / group_size;
     const int first_m = grp * FG_GROUP_M;
-    const int gm = min(FG_GROUP_M, a.tiles_m - first_m);
+    const int gm = min(FG_GROUP_M, tiles_m - first_m);
     const int rem = seq - grp * group_size;
     const int pm = first_m + rem % gm, pn = rem / gm;
     const int m0 = pm * FG_BM, n0 = pn * FG_BN;
-    if (m0 >= M) return;
 
     FgOperand<A_KM> opa;
     FgOperand<B_KM> opb;
