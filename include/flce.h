@@ -202,7 +202,9 @@ FLCE_API size_t flce_get_logits_budget_bytes(void);
  * host synchronisation).  The results are the same (dW sums the same non-zero
  * terms in other groups); the time of a chunk shrinks with its share of ignored
  * rows, in steps of the 256-row tiles.  Only problems that run entirely on the
- * tuned kernel are compacted.  Off: every row is projected. */
+ * tuned kernel are compacted.  Off: every row is projected; for batches known to
+ * have no ignored row that saves the gather and scatter copies (about 0.5 % of
+ * the time at V = 128K, 1 % at V = 32K). */
 FLCE_API int flce_set_row_compaction(int on);
 FLCE_API int flce_get_row_compaction(void);
 
