@@ -436,17 +436,28 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                     fg_value(raw_a[1][i]), fg_value(raw_b[1][j]), acc[i][j], 0, 0, 0);
     }
-    // the loads of the tiles past the end still target LDS: let them land before
-    // the workgroup can retire and its LDS be handed to another one
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // The loads of the tiles past the end still target LDS: let them land, for every
+    // wavefront of the workgroup, before LDS is reused below (and before the workgroup can
+    // retire and its LDS be handed to another one).
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
 
     // ---- epilogue.  Accumulator register g of lane l is row 8*(g/4)+4*(l/32)+g%4,
-    // column l%32 of its 32 x 32 tile.  Loads and stores go through buffer
-    // descriptors that cover the tile's valid rows (rows past M are dropped by the
-    // range check); the part of the address that is the same for the whole
-    // wavefront travels in a scalar register, so no per-element 64-bit address
-    // arithmetic is needed. ----
+    // column l%32 of its 32 x 32 tile: written straight from the registers, every store
+    // instruction would move one element per lane.  The memory pipe's cost is per
+    // instruction (about 9 cycles of the CU's address unit per wavefront-wide store,
+    // whatever it carries: measured), so the tile goes through LDS instead, which is
+    // free now: each wavefront stages 32 rows x 128 columns of its 128 x 128 sub-tile
+    // as fp32 in its own LDS region, reads them back row-major, 16 bytes of output per
+    // lane (4 fp32 or 8 bf16 consecutive columns), adds the addend (loaded with the
+    // same wide, row-contiguous accesses) and stores 16 bytes per lane: 16 or 8 times
+    // fewer memory instructions, each writing whole row segments.  Loads and stores go
+    // through buffer descriptors that cover the tile's valid rows (rows past M are
+    // dropped by the range check). ----
     constexpr int ES = (int)sizeof(OutT);
+    constexpr int EW = 16 / ES;                 // output elements per lane and access: 4 or 8
+    constexpr int LANES_PER_ROW = 128 / EW;     // 32 or 16
+    constexpr int ROWS_PER_ACCESS = 64 / LANES_PER_ROW;   // rows one wavefront-wide access covers: 2 or 4
+    constexpr int PITCH = 128 + 8;              // fp32 words per staged row: lanes 32..63 (4 rows on) hit the other banks
     const int frow = lane & 31, fhalf = lane >> 5;
     const int rows_c = min(FG_BM, M - m0);
     const int ldc = (int)a.ldc, ldcin = (int)a.ldcin;
@@ -458,50 +469,87 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
         rsrc_in = fg_make_rsrc(static_cast<const unsigned char*>(a.Cin) + (int64_t)m0 * a.ldcin * IS,
                                (uint32_t)rows_c * (uint32_t)ldcin * (uint32_t)IS);
     const int uwm = __builtin_amdgcn_readfirstlane(wm), uwn = __builtin_amdgcn_readfirstlane(wn);
-    const int lane_off = (4 * fhalf * ldc + frow) * ES;
-    const int lane_off_in = (4 * fhalf * ldcin + frow) * IS;
-    // Addend of one 32 x 32 tile of this wavefront (16 loads); issued one tile ahead of
-    // its use so that the loads' latency hides behind the previous tile's stores.
-    auto load_addend = [&](int t, float (&old)[16]) __attribute__((always_inline)) {
-        const int i = t & 3, j = t >> 2;
-        const int row0 = uwm * 128 + i * 32, col0 = n0 + uwn * 128 + j * 32;
+    float* stage = reinterpret_cast<float*>(smem + uwave * (FG_LDS_BYTES / 4));   // 40 KB per wavefront
+    // output mapping of the lane: row (inside a group of ROWS_PER_ACCESS) and first column
+    const int orow = lane / LANES_PER_ROW, ocol = (lane % LANES_PER_ROW) * EW;
+    const int colw = n0 + uwn * 128;                       // first column of the wavefront's sub-tile
+    // columns are written in groups of EW; C rows must be allocated up to N rounded up to EW
+    const bool col_ok = colw + ocol < ((a.N + EW - 1) / EW) * EW;
+    const int lane_off = (orow * ldc + ocol) * ES;
+    const int lane_off_in = (orow * ldcin + ocol) * IS;
+    constexpr int NACC = 32 / ROWS_PER_ACCESS;             // accesses per 32-row pass: 16 or 8
+    constexpr int INW = HAS_IN ? EW * IS / 4 : 1;          // dwords of addend per lane and access
 #pragma unroll
-        for (int g = 0; g < 16; ++g) {
-            const int soff = ((row0 + 8 * (g >> 2) + (g & 3)) * ldcin + col0) * IS;
-            if constexpr (IS == 4)
-                old[g] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc_in, lane_off_in, soff, 0));
-            else   // bf16 addend: its 16 bits are the high half of the float
-                old[g] = __uint_as_float(
-                    (unsigned)__builtin_amdgcn_raw_buffer_load_b16(rsrc_in, lane_off_in, soff, 0) << 16);
-        }
-    };
-    float old[2][16];
-    if constexpr (HAS_IN) load_addend(0, old[0]);
+    for (int i = 0; i < 4; ++i) {                          // pass: rows 32 i .. 32 i + 31 of the sub-tile
+        const int row0 = uwm * 128 + i * 32;
+        uint32_t old[NACC][INW];
+        if constexpr (HAS_IN) {                            // the pass's addend, before anything waits on it
 #pragma unroll
-    for (int t = 0; t < 16; ++t) {   // tile t: i = t % 4 (rows), j = t / 4 (columns)
-        const int i = t & 3, j = t >> 2;
-        const int row0 = uwm * 128 + i * 32, col0 = n0 + uwn * 128 + j * 32;
-        if constexpr (HAS_IN) {
-            if (t + 1 < 16) load_addend(t + 1, old[(t + 1) & 1]);
+            for (int k = 0; k < NACC; ++k) {
+                const int soff = ((row0 + k * ROWS_PER_ACCESS) * ldcin + colw) * IS;
+                if constexpr (INW == 4) {
+                    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc_in, lane_off_in, soff, 0);
 #pragma unroll
-            for (int g = 0; g < 16; ++g) acc[i][j][g] += old[t & 1][g];
-        }
-        if (col0 + frow < a.N) {
+                    for (int e = 0; e < 4; ++e) old[k][e] = v[e];
+                } else if constexpr (INW == 8) {
+                    const u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(rsrc_in, lane_off_in, soff, 0);
+                    const u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(rsrc_in, lane_off_in + 16, soff, 0);
 #pragma unroll
-            for (int g = 0; g < 16; ++g) {
-                const int soff = ((row0 + 8 * (g >> 2) + (g & 3)) * ldc + col0) * ES;
-                // read the element into a scalar first: a bit_cast applied directly
-                // to an accumulator vector element is miscompiled by this toolchain
-                const float v = acc[i][j][g];
-                if constexpr (ES == 4) {
-                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rsrc_c, lane_off, soff, 0);
-                } else {
-                    __builtin_amdgcn_raw_buffer_store_b16(
-                        __builtin_bit_cast(unsigned short, from_f32<bf16_t>(v)), rsrc_c, lane_off, soff,
-                        0);
+                    for (int e = 0; e < 4; ++e) {
+                        old[k][e] = v0[e];
+                        old[k][4 + e] = v1[e];
+                    }
+                } else {   // 8 bf16 = 4 dwords, or 4 bf16 = 2 dwords
+                    static_assert(INW == 2, "addend width");
+                    const auto v = __builtin_amdgcn_raw_buffer_load_b64(rsrc_in, lane_off_in, soff, 0);
+                    old[k][0] = v[0];
+                    old[k][1] = v[1];
                 }
             }
         }
+        // stage the pass: element (row 8*(g/4)+4*fhalf+g%4, column 32 j + frow)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int g = 0; g < 16; ++g) {
+                // read the element into a scalar first: a bit_cast applied directly
+                // to an accumulator vector element is miscompiled by this toolchain
+                const float v = acc[i][j][g];
+                stage[(8 * (g >> 2) + 4 * fhalf + (g & 3)) * PITCH + 32 * j + frow] = v;
+            }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < NACC; ++k) {
+            const float* src = stage + (k * ROWS_PER_ACCESS + orow) * PITCH + ocol;
+            float v[EW];
+#pragma unroll
+            for (int e = 0; e < EW; e += 4) {
+                const f32x4 q = *reinterpret_cast<const f32x4*>(src + e);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) v[e + u] = q[u];
+            }
+            if constexpr (HAS_IN) {
+#pragma unroll
+                for (int e = 0; e < EW; ++e) {
+                    if constexpr (IS == 4) v[e] += __uint_as_float(old[k][e]);
+                    else v[e] += __uint_as_float((e & 1) ? (old[k][e >> 1] & 0xffff0000u) : (old[k][e >> 1] << 16));
+                }
+            }
+            const int soff = ((row0 + k * ROWS_PER_ACCESS) * ldc + colw) * ES;
+            u32x4 out;
+            if constexpr (ES == 4) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) out[e] = __float_as_uint(v[e]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bf16x2 p2 = {from_f32<bf16_t>(v[2 * e]), from_f32<bf16_t>(v[2 * e + 1])};
+                    out[e] = __builtin_bit_cast(uint32_t, p2);
+                }
+            }
+            if (col_ok) __builtin_amdgcn_raw_buffer_store_b128(out, rsrc_c, lane_off, soff, 0);
+        }
+        __syncthreads();   // the region is rewritten by the next pass
     }
 }
 
