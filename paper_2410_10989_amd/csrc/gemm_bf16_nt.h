@@ -350,7 +350,7 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
         const unsigned sa_addr = lds0 + SA * FG_TILE_BYTES, sb_addr = lds0 + SB * FG_TILE_BYTES;
         __builtin_amdgcn_sched_barrier(0);
 #define FG_MFMA(q) \
-        acc[(q) >> 2][(q) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[(q) >> 2], fb[(q) & 3], acc[(q) >> 2][(q) & 3], 0, 0, 0)
+        acc[(q) >> 2][(q) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[(q) & 3], fa[(q) >> 2], acc[(q) >> 2][(q) & 3], 0, 0, 0)
 #define FG_DMA(n)                                                          \
         if constexpr (DMA == 1) opb.load_one(smem, SD, kt, uwave, R0 + (n));   \
         if constexpr (DMA == 2) opa.load_one(smem, SD, kt, uwave, R0 + (n))
@@ -434,16 +434,17 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    fg_value(raw_a[1][i]), fg_value(raw_b[1][j]), acc[i][j], 0, 0, 0);
+                    fg_value(raw_b[1][j]), fg_value(raw_a[1][i]), acc[i][j], 0, 0, 0);
     }
     // The loads of the tiles past the end still target LDS: let them land, for every
     // wavefront of the workgroup, before LDS is reused below (and before the workgroup can
     // retire and its LDS be handed to another one).
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
 
-    // ---- epilogue.  Accumulator register g of lane l is row 8*(g/4)+4*(l/32)+g%4,
-    // column l%32 of its 32 x 32 tile: written straight from the registers, every store
-    // instruction would move one element per lane.  The memory pipe's cost is per
+    // ---- epilogue.  The MFMAs are fed the B fragment first and the A fragment second, so
+    // accumulator register g of lane l is ROW l%32, column 8*(g/4)+4*(l/32)+g%4 of its
+    // 32 x 32 tile: four consecutive columns per group of four registers.  Written straight
+    // from the registers, a store instruction would touch 32 different rows.  The memory pipe's cost is per
     // instruction (about 9 cycles of the CU's address unit per wavefront-wide store,
     // whatever it carries: measured), so the tile goes through LDS instead, which is
     // free now: each wavefront stages 32 rows x 128 columns of its 128 x 128 sub-tile
@@ -457,7 +458,7 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
     constexpr int EW = 16 / ES;                 // output elements per lane and access: 4 or 8
     constexpr int LANES_PER_ROW = 128 / EW;     // 32 or 16
     constexpr int ROWS_PER_ACCESS = 64 / LANES_PER_ROW;   // rows one wavefront-wide access covers: 2 or 4
-    constexpr int PITCH = 128 + 8;              // fp32 words per staged row: lanes 32..63 (4 rows on) hit the other banks
+    constexpr int PITCH = 128 + 4;              // fp32 words per staged row: 16 lanes' 16-byte writes of one column group hit 64 different banks
     const int frow = lane & 31, fhalf = lane >> 5;
     const int rows_c = min(FG_BM, M - m0);
     const int ldc = (int)a.ldc, ldcin = (int)a.ldcin;
@@ -507,15 +508,20 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
                 }
             }
         }
-        // stage the pass: element (row 8*(g/4)+4*fhalf+g%4, column 32 j + frow)
+        // stage the pass: the lane holds row frow and, per group of four registers, the four
+        // consecutive columns 32 j + 8 (g/4) + 4 fhalf .. + 3 (the MFMAs are fed B first, A
+        // second, so the accumulators hold the transposed 32 x 32 tiles): one 16-byte LDS
+        // write per group
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int g = 0; g < 16; ++g) {
-                // read the element into a scalar first: a bit_cast applied directly
+            for (int g4 = 0; g4 < 4; ++g4) {
+                // read the elements into scalars first: a bit_cast applied directly
                 // to an accumulator vector element is miscompiled by this toolchain
-                const float v = acc[i][j][g];
-                stage[(8 * (g >> 2) + 4 * fhalf + (g & 3)) * PITCH + 32 * j + frow] = v;
+                const float v0 = acc[i][j][4 * g4], v1 = acc[i][j][4 * g4 + 1], v2 = acc[i][j][4 * g4 + 2],
+                            v3 = acc[i][j][4 * g4 + 3];
+                const f32x4 q = {v0, v1, v2, v3};
+                *reinterpret_cast<f32x4*>(stage + frow * PITCH + 32 * j + 8 * g4 + 4 * fhalf) = q;
             }
         __syncthreads();
 #pragma unroll
