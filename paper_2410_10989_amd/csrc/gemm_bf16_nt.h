@@ -523,7 +523,11 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
                 const f32x4 q = {v0, v1, v2, v3};
                 *reinterpret_cast<f32x4*>(stage + frow * PITCH + 32 * j + 8 * g4 + 4 * fhalf) = q;
             }
-        __syncthreads();
+        // The region is private to the wavefront and LDS executes a wavefront's accesses in
+        // order: no workgroup barrier is needed, only that the compiler keeps the order (a
+        // barrier of the usual kind would also wait for the global stores of the previous
+        // pass to be acknowledged: measured 1 000 cycles per pass).
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
         for (int k = 0; k < NACC; ++k) {
             const float* src = stage + (k * ROWS_PER_ACCESS + orow) * PITCH + ocol;
@@ -555,7 +559,7 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
             }
             if (col_ok) __builtin_amdgcn_raw_buffer_store_b128(out, rsrc_c, lane_off, soff, 0);
         }
-        __syncthreads();   // the region is rewritten by the next pass
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next pass rewrites the region
     }
 }
 
