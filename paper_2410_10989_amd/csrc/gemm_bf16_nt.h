@@ -42,6 +42,11 @@
 //    selects the XCD and each XCD walks its own contiguous span of a grouped
 //    (8 tile rows at a time) tile order; tiles that run together on one XCD
 //    share A and B panels in that XCD's L2.
+//  - epilogue through LDS: the MFMAs take the B fragment first and the A fragment
+//    second, so a lane's accumulators are four consecutive columns of one row per
+//    register quad; each wavefront stages 32 x 128 values at a time in its own LDS
+//    region and writes 16 bytes of output per lane, whole row segments per
+//    instruction (the memory pipe charges per store instruction).
 // With ksplit > 1 the K range is cut into ksplit pieces computed by different
 // workgroups; piece s writes its partial result to C + s * split_stride (fp32), and a
 // separate fixed-order reduction adds the pieces (used when M x N has fewer tiles
