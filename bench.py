@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 # the same counter reads for the 1 GiB copy of --calibrate-copy; the summary of
 # those runs is profiles/gemm_bf16_256_config3_hbm_traffic.txt.  Only valid for
 # the default workload.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 8.61e9
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 9.35e9
 
 
 def bench_cross_entropy(args):

@@ -116,20 +116,27 @@ int acquire_workspace(size_t need, char** out) {
     return FLCE_OK;
 }
 
-// C[M x N] (+)= A[M x K] * B[N x K]^T on the generic guarded kernel.
+// C[M x N] (+)= A[M x K] * B[N x K]^T on the generic guarded kernel.  With ksplit > 1
+// K is cut into ksplit ranges and range z writes its partial result to
+// C + z * split_stride (no accumulation then).
 template <typename T, typename OutT>
 int launch_gemm_generic(int kind, const T* A, int64_t lda, const T* B, int64_t ldb, OutT* C,
-                        int64_t ldc, int64_t M, int64_t N, int64_t K, bool accum, hipStream_t s) {
+                        int64_t ldc, int64_t M, int64_t N, int64_t K, bool accum, hipStream_t s,
+                        int ksplit = 1, int64_t split_stride = 0) {
     if (M <= 0 || N <= 0) return FLCE_OK;
+    if (ksplit > 1 && accum) return FLCE_ERR_SHAPE;
     ScopedKernelTimer timer(kind, s);
     constexpr int VEC = GGTraits<T>::VEC;
+    constexpr int BK = GGTraits<T>::BK;
     const bool al = (K % VEC == 0) && (lda % VEC == 0) && (ldb % VEC == 0) && aligned(A, 16) &&
                     aligned(B, 16);
-    dim3 grid((unsigned)((N + GG_BN - 1) / GG_BN), (unsigned)((M + GG_BM - 1) / GG_BM));
+    const int64_t k_per = round_up((K + ksplit - 1) / ksplit, BK);
+    dim3 grid((unsigned)((N + GG_BN - 1) / GG_BN), (unsigned)((M + GG_BM - 1) / GG_BM),
+              (unsigned)ksplit);
     dim3 block(GG_THREADS);
 #define GG_LAUNCH(AL, AC)                                                                       \
     hipLaunchKernelGGL((gemm_nt_generic<T, OutT, AL, AC>), grid, block, 0, s, A, lda, B, ldb, C, \
-                       ldc, (int)M, (int)N, (int)K)
+                       ldc, (int)M, (int)N, (int)K, (int)k_per, split_stride)
     if (al) {
         if (accum) GG_LAUNCH(true, true); else GG_LAUNCH(true, false);
     } else {
@@ -343,8 +350,23 @@ int run_head(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t
                     }
                 }
             } else {
-                FLCE_TRY((launch_gemm_generic<T, T>(FLCE_KIND_DX_GEMM, Z, p.ldz, WT, p.ldz, dXc, H, rows,
-                                                    H, V, add_in_gemm, s)));
+                if (p.dx_ksplit > 1) {
+                    float* part = reinterpret_cast<float*>(ws + p.off_dxpart);
+                    FLCE_TRY((launch_gemm_generic<T, float>(FLCE_KIND_DX_GEMM, Z, p.ldz, WT, p.ldz, part,
+                                                            H, rows, H, V, false, s, p.dx_ksplit,
+                                                            p.C * H)));
+                    ScopedKernelTimer timer(FLCE_KIND_DX_GEMM, s);
+                    if (add_in_gemm)
+                        hipLaunchKernelGGL((splitk_reduce_kernel<T, true>), dim3(1024), dim3(256), 0, s,
+                                           part, p.C * H, p.dx_ksplit, dXc, rows * H);
+                    else
+                        hipLaunchKernelGGL((splitk_reduce_kernel<T, false>), dim3(1024), dim3(256), 0, s,
+                                           part, p.C * H, p.dx_ksplit, dXc, rows * H);
+                    HIP_TRY(hipGetLastError());
+                } else {
+                    FLCE_TRY((launch_gemm_generic<T, T>(FLCE_KIND_DX_GEMM, Z, p.ldz, WT, p.ldz, dXc, H,
+                                                        rows, H, V, add_in_gemm, s)));
+                }
             }
             if (norm) {
                 ScopedKernelTimer timer(FLCE_KIND_OTHER, s);

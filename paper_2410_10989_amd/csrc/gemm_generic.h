@@ -5,6 +5,10 @@
 // fp32 storage type (true fp32 products on v_mfma_f32_32x32x2_f32) and every
 // bf16 shape the tuned kernel does not take (ragged or unaligned).
 //
+// A launch can cut K into ranges (grid z), each writing a partial result of its own:
+// products with few output tiles and a long K (dX of a small batch) fill the chip
+// that way; the partial results are summed in a fixed order by splitk_reduce_kernel.
+//
 // Workgroup: 256 threads = 4 wavefronts in a 2 x 2 arrangement; macro tile
 // 128 x 128, K step 64 bytes per row; each wavefront owns a 64 x 64 quadrant
 // as 2 x 2 MFMA 32 x 32 tiles with fp32 accumulators.
@@ -54,7 +58,8 @@ template <typename T, typename OutT, bool ALIGNED, bool ACCUM>
 __global__ __launch_bounds__(GG_THREADS) void gemm_nt_generic(const T* __restrict__ A, int64_t lda,
                                                               const T* __restrict__ B, int64_t ldb,
                                                               OutT* __restrict__ C, int64_t ldc,
-                                                              int M, int N, int K) {
+                                                              int M, int N, int K, int k_per,
+                                                              int64_t split_stride) {
     using TR = GGTraits<T>;
     __shared__ __attribute__((aligned(16))) unsigned char lds_a[GG_BM * GG_LDS_ROW];
     __shared__ __attribute__((aligned(16))) unsigned char lds_b[GG_BN * GG_LDS_ROW];
@@ -63,6 +68,11 @@ __global__ __launch_bounds__(GG_THREADS) void gemm_nt_generic(const T* __restric
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int m0 = blockIdx.y * GG_BM, n0 = blockIdx.x * GG_BN;
+    // K range of this workgroup: blockIdx.z counts ranges of k_per elements (a multiple of
+    // the K step), each with a result matrix of its own, split_stride elements apart
+    const int k_begin = blockIdx.z * k_per;
+    K = min(K, k_begin + k_per);
+    C += (int64_t)blockIdx.z * split_stride;
 
     f32x16 acc[2][2];
 #pragma unroll
@@ -75,7 +85,7 @@ __global__ __launch_bounds__(GG_THREADS) void gemm_nt_generic(const T* __restric
     // staging: 128 rows x 4 vectors per operand tile, 2 vectors per thread
     const int ld_row = tid >> 2, ld_vec = tid & 3;
 
-    for (int k0 = 0; k0 < K; k0 += TR::BK) {
+    for (int k0 = k_begin; k0 < K; k0 += TR::BK) {
         u32x4 ra[2], rb[2];
 #pragma unroll
         for (int h = 0; h < 2; ++h) {

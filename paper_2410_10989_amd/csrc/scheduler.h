@@ -67,6 +67,17 @@ inline int max_dx_ranges(size_t budget_bytes, int64_t rows, int64_t H) {
     return (int)std::max<size_t>(1, std::min<size_t>(n, 16));
 }
 
+// K ranges of the dX product (rows x H output, K = V).  The tuned kernel works on
+// 256 x 256 tiles and K steps of 64; the guarded kernel on 128 x 128 tiles, where a
+// range is at least 256 elements long.
+inline int dx_ranges(bool tuned, int64_t rows, int64_t H, int64_t V, size_t budget_bytes) {
+    if (tuned)
+        return choose_ksplit(((rows + 255) / 256) * ((H + 255) / 256), (V + 63) / 64,
+                             max_dx_ranges(budget_bytes, round_up(rows, 256), H));
+    return choose_ksplit(((rows + 127) / 128) * ((H + 127) / 128), V / 4,
+                         max_dx_ranges(budget_bytes, round_up(rows, 128), H));
+}
+
 // Limits of the tuned kernel's 32-bit offsets inside one tile (see gemm_bf16_nt.h).
 inline bool fits_row_form(int64_t ld, int64_t) { return 256 * ld * 2 + 128 < ((int64_t)1 << 30); }
 inline bool fits_col_form(int64_t ld, int64_t) { return 64 * ld * 2 + 512 < ((int64_t)1 << 30); }
@@ -110,10 +121,9 @@ inline Plan make_plan(int64_t BT, int64_t H, int64_t V, int dtype, size_t budget
         p.fast_dw_full = (p.nchunks > 1) ? dw_ok(p.C) : dw_ok(rows_last);
         p.fast_dw_last = dw_ok(rows_last);
     }
-    if (p.fast_dx) {
+    {
         const int64_t rows = p.nchunks > 1 ? p.C : rows_last;
-        p.dx_ksplit = choose_ksplit(((rows + 255) / 256) * ((H + 255) / 256), (V + 63) / 64,
-                                    max_dx_ranges(budget_bytes, round_up(rows, 256), H));
+        p.dx_ksplit = dx_ranges(p.fast_dx, rows, H, V, budget_bytes);
     }
     p.compact = allow_compact && p.fast_logits && p.fast_dx && p.fast_dw_full && p.fast_dw_last;
     const bool need_wt = !p.fast_dx;
@@ -133,11 +143,11 @@ inline Plan make_plan(int64_t BT, int64_t H, int64_t V, int dtype, size_t budget
     p.off_xt = take(need_gt ? (size_t)H * p.ldc * es : 0);
     p.off_dwacc = take(p.fp32_dw_acc ? (size_t)V * H * sizeof(float) : 0);
     size_t dxpart = p.dx_ksplit > 1 ? (size_t)p.dx_ksplit * p.C * H * sizeof(float) : 0;
-    if (worst_case_bt && p.fast_dx) {
-        // the bound has to hold for every chunk size the scheduler can pick
-        for (int64_t c = CHUNK_ALIGN; c <= cmax; c += CHUNK_ALIGN) {
-            const int ks = choose_ksplit((c / 256) * ((H + 255) / 256), (V + 63) / 64,
-                                         max_dx_ranges(budget_bytes, c, H));
+    if (worst_case_bt) {
+        // the bound has to hold for every chunk size the scheduler can pick (the number of
+        // ranges depends on the row count through its count of 128-row tiles only)
+        for (int64_t c = 128; c <= cmax; c += 128) {
+            const int ks = dx_ranges(p.fast_dx, c, H, V, budget_bytes);
             if (ks > 1) dxpart = std::max(dxpart, (size_t)ks * c * H * sizeof(float));
         }
     }

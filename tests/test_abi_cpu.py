@@ -76,7 +76,8 @@ def test_dx_product_is_cut_along_k_to_fill_whole_rounds_of_cus():
     assert k(16384, 3584, 152064, code) >= 4      # chunks of 3328 rows: 13 x 14 = 182 tiles
     assert k(8192, 2304, 256000, code) >= 3       # chunks of 2048 rows: 8 x 9 = 72 tiles
     assert k(65536, 4096, 32000, code) == 1       # 16384-row chunks: 1024 tiles, many rounds
-    assert k(256, 512, 4096, flce.FLCE_F32) == 1  # fp32 storage runs on the guarded kernels
+    assert k(256, 512, 4096, flce.FLCE_F32) == 16 # guarded kernels (fp32 storage): 2 x 4 tiles of 128 x 128
+    assert k(4096, 4096, 32000, flce.FLCE_F32) == 1
     for bt, h, v in [(4352, 4096, 8192), (16384, 3584, 152064), (8192, 2304, 256000)]:
         # the fp32 partial results are part of the reported workspace and stay within the budget
         c = flce.flce_chunk_rows(bt, h, v, code)
