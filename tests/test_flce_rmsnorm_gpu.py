@@ -12,7 +12,7 @@ pytestmark = pytest.mark.gpu
 
 
 def make_case(BT, H, V, dtype, seed, ignore=("iid", 0.1)):
-    # raw hidden states with a spread of row scales; gamma around 1
+    # raw hidden states with a spread of row scales; gamma close to one
     w = workloads.make(BT, H, V, dtype, ignore=ignore, seed=seed, name="rmsnorm", x_std=2.5)
     g = np.random.Generator(np.random.Philox(key=[seed, 99]))
     gamma = (1.0 + 0.2 * g.standard_normal(H)).astype(np.float32)
