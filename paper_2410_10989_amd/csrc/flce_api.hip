@@ -161,6 +161,7 @@ int launch_gemm_fast(int kind, const bf16_t* A, int64_t lda, const bf16_t* B, in
              (int)((M + FG_BM - 1) / FG_BM), (int)((N + FG_BN - 1) / FG_BN), ksplit, split_stride,
              dyn_rows, dyn_is_k};
     const int64_t total = (int64_t)a.tiles_m * a.tiles_n * ksplit;
+    if (total >= ((int64_t)1 << 30)) return FLCE_ERR_SHAPE;   // the kernel counts tiles in 32 bits
     const dim3 grid((unsigned)((total + FG_XCDS - 1) / FG_XCDS * FG_XCDS));
     hipLaunchKernelGGL((gemm_bf16_256<OutT, InT, A_KM, B_KM>), grid, dim3(FG_THREADS), 0, s, a);
     HIP_TRY(hipGetLastError());
