@@ -78,6 +78,31 @@ def test_several_chunks_with_ragged_last_chunk(dtype):
         flce.flce_set_logits_budget_bytes(old)
 
 
+def _random_cases(n, seed):
+    import random
+    rng = random.Random(seed)
+    cases = []
+    for k in range(n):
+        cases.append((rng.choice(["f32", "bf16"]), rng.choice([1, 7, 64, 130, 257, 600, 1100]),
+                      rng.choice([8, 24, 64, 72, 136, 256, 520]),
+                      rng.choice([3, 64, 257, 1000, 2048, 5003, 9000]),
+                      rng.choice([("none",), ("iid", 0.2), ("iid", 0.7)]), rng.choice([0, 256, 512]), k))
+    return cases
+
+
+@pytest.mark.parametrize("dtype,BT,H,V,ignore,budget_rows,k", _random_cases(32, 20241010))
+def test_random_shapes_and_budgets(dtype, BT, H, V, ignore, budget_rows, k):
+    # seeded draws over both storage types, ragged and tiny dimensions, few-tile dX
+    # products (cut along K) and logits budgets of 256 / 512 rows (several chunks)
+    import paper_2410_10989_amd as flce
+    old = flce.flce_get_logits_budget_bytes()
+    try:
+        flce.flce_set_logits_budget_bytes(budget_rows * ((V + 63) // 64 * 64) * (4 if dtype == "f32" else 2))
+        check_full(workloads.make(BT, H, V, dtype, ignore=ignore, seed=7000 + k, name="random"))
+    finally:
+        flce.flce_set_logits_budget_bytes(old)
+
+
 def test_zipf_targets_medium_bf16():
     check_full(workloads.make(1024, 512, 8192, "bf16", targets="zipf", ignore=("iid", 0.05),
                               seed=99, name="zipf"))
