@@ -100,6 +100,8 @@ def main():
                     help="frozen backbone (Medusa stage 1): no hidden-state gradient")
     ap.add_argument("--no-compaction", action="store_true",
                     help="project every row, also those with an ignored target (A/B of the row compaction)")
+    ap.add_argument("--no-mfma-loop", action="store_true",
+                    help="skip the MFMA-only loop that is reported beside the roofline")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one plain 1 GiB device copy first (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -260,6 +262,34 @@ def main():
                      "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH
                      if args.config == 3 and dom == "logits_gemm" and not args.budget_mib else None},
     }
+
+    if w.dtype == "bf16" and not args.no_mfma_loop:
+        # What the matrix pipes sustain with nothing to feed them from memory: the same MFMA
+        # instruction in a loop on register operands, one wavefront per SIMD, launches about
+        # as long as a product launch.  On operands like the workload's (normal deviates,
+        # 4 x 4 fragments per K sub-step) the chip clocks far lower than on zeros.
+        scratch = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
+
+        def mfma_loop(pattern):
+            # a train of launches back to back, as long as a few passes of the path: the clock
+            # settles within the first launches, which are left out
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            fl = 0.0
+            for k in range(16):
+                if k == 4:
+                    e0.record()
+                one = flce.flce_mfma_ceiling_launch(pattern, 256, 8000, 0.02, scratch)
+                fl += one if k >= 4 else 0.0
+            e1.record()
+            e1.synchronize()
+            return fl / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+        rnd, zero = mfma_loop(2), mfma_loop(0)
+        out["mfma_only_loop"] = {
+            "random_operands_tflops": rnd, "zero_operands_tflops": zero,
+            "what": "v_mfma_f32_32x32x16_bf16 on register operands, no memory traffic, 256 workgroups x 4 "
+                    "wavefronts, 12 launches of ~3 ms back to back after 4 to settle the clock; random = N(0,1) x N(0,0.02^2) fragments, 4 A x 4 B per 16 MFMAs"}
+        out["roofline"]["frac_of_mfma_only_loop_random"] = achieved / rnd if rnd > 0 else None
 
     if not args.no_cpu_baseline:
         from oracle import flce_oracle

@@ -243,6 +243,20 @@ typedef enum {
 FLCE_API int flce_timing_enable(int on);
 FLCE_API int flce_timing_collect(double* total_ms, int64_t* launches);
 
+/* Measurement aid, not part of the path (benchmarks report it beside the product
+ * kernels' rate): enqueues on `stream` one launch of `workgroups` workgroups (4
+ * wavefronts each, one per SIMD: 256 fill the chip) that execute iters * 16
+ * v_mfma_f32_32x32x16_bf16 per wavefront on register operands and touch no memory
+ * but `out` (device, at least workgroups * 256 floats, overwritten with checksums).
+ * pattern 0: zero operands; 1: one fixed pair of fragments; 2: 4 A x 4 B fragments
+ * per wavefront in the order of a K sub-step of the product kernel, A ~ N(0,1),
+ * B ~ N(0, std_b^2), rounded to bf16.  Work: workgroups * 4 * iters * 16 * 32768
+ * flops.  The sustained rate depends on the pattern because the chip lowers its
+ * clock as more operand bits toggle; pattern 2 is the ceiling for products of such
+ * data.  FLCE_ERR_ARG for sizes out of range (iters <= 2^24, workgroups <= 65536). */
+FLCE_API int flce_mfma_ceiling_launch(int pattern, int workgroups, int iters, float std_b, float* out,
+                                      size_t out_floats, void* stream);
+
 FLCE_API const char* flce_status_string(int status);
 
 #ifdef __cplusplus

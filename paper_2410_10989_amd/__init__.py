@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     flce_release_workspace, flce_set_logits_budget_bytes, flce_set_workspace,
     flce_workspace_bytes,
     flce_workspace_bytes_max, lib, status_string, flce_timing_enable, flce_timing_collect,
+    flce_mfma_ceiling_launch,
     KERNEL_KINDS,
 )
 

@@ -54,6 +54,7 @@ def lib() -> ctypes.CDLL:
             "flce_dx_k_ranges": ([i64, i64, i64, ci], ci),
             "flce_paper_chunk_rows": ([i64, i64, i64], i64),
             "flce_full_logits_bytes": ([i64, i64, ci], sz),
+            "flce_mfma_ceiling_launch": ([ci, ci, ci, ctypes.c_float, p, sz, p], ci),
             "flce_timing_enable": ([ci], ci),
             "flce_timing_collect": ([p, p], ci),
             "flce_status_string": ([ci], ctypes.c_char_p),
@@ -295,6 +296,17 @@ def flce_full_logits_bytes(BT, V, dtype) -> int:
 
 
 KERNEL_KINDS = ("logits_gemm", "ce_rows", "dx_gemm", "dw_gemm", "other")
+
+
+def flce_mfma_ceiling_launch(pattern: int, workgroups: int, iters: int, std_b: float, out, stream=None):
+    """Enqueues the MFMA-only loop (see include/flce.h); `out` is a float32 CUDA tensor
+    of at least workgroups * 256 elements.  Returns the flops of the launch."""
+    if out.dtype != torch.float32 or not out.is_cuda or not out.is_contiguous():
+        raise ValueError("out must be a contiguous float32 CUDA tensor")
+    _check(lib().flce_mfma_ceiling_launch(int(pattern), int(workgroups), int(iters), float(std_b),
+                                          out.data_ptr(), out.numel(), _stream_handle(stream)),
+           "flce_mfma_ceiling_launch")
+    return workgroups * 4 * iters * 16 * 32768.0
 
 
 def flce_timing_enable(on: bool):

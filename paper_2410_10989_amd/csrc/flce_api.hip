@@ -10,6 +10,7 @@
 #include "flce_device.h"
 #include "gemm_bf16_nt.h"
 #include "gemm_generic.h"
+#include "mfma_ceiling.h"
 #include "misc_kernels.h"
 #include "rmsnorm.h"
 #include "rowreduce.h"
@@ -714,6 +715,21 @@ int64_t flce_paper_chunk_rows(int64_t BT, int64_t H, int64_t V) {
 size_t flce_full_logits_bytes(int64_t BT, int64_t V, int dtype) {
     if (BT <= 0 || V <= 0 || (dtype != FLCE_F32 && dtype != FLCE_BF16)) return 0;
     return (size_t)BT * (size_t)V * elem_size(dtype);
+}
+
+int flce_mfma_ceiling_launch(int pattern, int workgroups, int iters, float std_b, float* out,
+                             size_t out_floats, void* stream) {
+    if (!out) return FLCE_ERR_NULL;
+    if (pattern < 0 || pattern > 2 || workgroups <= 0 || workgroups > 65536 || iters <= 0 ||
+        iters > (1 << 24) || !(std_b >= 0.0f) || out_floats < (size_t)workgroups * 256)
+        return FLCE_ERR_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const dim3 grid((unsigned)workgroups), block(256);
+    if (pattern == 0) hipLaunchKernelGGL((mfma_ceiling_kernel<0>), grid, block, 0, s, out, iters, std_b);
+    if (pattern == 1) hipLaunchKernelGGL((mfma_ceiling_kernel<1>), grid, block, 0, s, out, iters, std_b);
+    if (pattern == 2) hipLaunchKernelGGL((mfma_ceiling_kernel<2>), grid, block, 0, s, out, iters, std_b);
+    HIP_TRY(hipGetLastError());
+    return FLCE_OK;
 }
 
 int flce_timing_enable(int on) {

@@ -313,3 +313,17 @@ def test_compaction_on_and_off_agree():
     assert err <= 2.0 ** -7 * off[2].float().abs().max().item()
     ref = oracle.flce(w.X, w.W, w.targets, w.ignore_index)
     assert_close("dW (compaction off)", to_host(off[2]), ref.dW, TOL["bf16"][1])
+
+
+def test_mfma_only_loop_runs_and_counts_its_flops():
+    # measurement aid: zero operands give zero checksums, random operands finite ones
+    import paper_2410_10989_amd as flce
+    out = torch.full((8 * 256,), float("nan"), device="cuda")
+    fl = flce.flce_mfma_ceiling_launch(0, 8, 10, 0.02, out)
+    torch.cuda.synchronize()
+    assert fl == 8 * 4 * 10 * 16 * 32768.0 and (out == 0).all()
+    flce.flce_mfma_ceiling_launch(2, 8, 10, 0.02, out)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all() and (out != 0).any()
+    with pytest.raises(flce.FlceError):
+        flce.flce_mfma_ceiling_launch(2, 9, 10, 0.02, out)       # out too small
