@@ -100,6 +100,8 @@ def main():
                     help="frozen backbone (Medusa stage 1): no hidden-state gradient")
     ap.add_argument("--no-compaction", action="store_true",
                     help="project every row, also those with an ignored target (A/B of the row compaction)")
+    ap.add_argument("--rmsnorm", action="store_true",
+                    help="time flce_rmsnorm_fwd_bwd: RMSNorm of raw hidden states fused in front (one head)")
     ap.add_argument("--no-mfma-loop", action="store_true",
                     help="skip the MFMA-only loop that is reported beside the roofline")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -169,6 +171,15 @@ def main():
         def step():
             flce.flce_multihead_fwd_bwd(X, Ws, ts, wts, w.ignore_index, loss=loss, head_losses=hl,
                                         dX=None if args.skip_dx else dX, dWs=dWs, flags=flags)
+    elif args.rmsnorm:
+        h_np, gamma_np = workloads.make_rmsnorm_inputs(w)
+        hraw, gamma = up(h_np), up(gamma_np)
+        dgamma = torch.empty_like(gamma)
+
+        def step():
+            flce.flce_rmsnorm_fwd_bwd(hraw, gamma, 1e-6, W, t, w.ignore_index, loss=loss,
+                                      dh=None if args.skip_dx else dX,
+                                      dgamma=None if args.skip_dx else dgamma, dW=dW, flags=flags)
     else:
         def step():
             flce.flce_fwd_bwd(X, W, t, w.ignore_index, loss=loss, dX=None if args.skip_dx else dX,
@@ -222,8 +233,9 @@ def main():
     ce_gbs = (2.0 * w.BT * w.V * (2 if w.dtype == "bf16" else 4) * args.steps) / (ce_ms * 1e-3) / 1e9 if ce_n else 0.0
 
     out = {
-        "metric": "FLCE fwd+bwd tokens/s" if nh == 1 and not args.skip_dx else
-                  f"FLCE fwd+bwd tokens/s, {nh} head(s)" + (", no dX" if args.skip_dx else ""),
+        "metric": ("RMSNorm + " if args.rmsnorm else "") +
+                  ("FLCE fwd+bwd tokens/s" if nh == 1 and not args.skip_dx else
+                   f"FLCE fwd+bwd tokens/s, {nh} head(s)" + (", no dX" if args.skip_dx else "")),
         "value": tokens_per_s,
         "unit": "tokens/s",
         "n_gpus": 1,
@@ -248,7 +260,8 @@ def main():
         "row_compaction": bool(compaction),
         "rows_projected": rows_projected,
         "tflops_executed": tflops * rows_projected / (w.BT * nh),
-        "peak_extra_hbm_mb": flce.flce_workspace_bytes(w.BT, w.H, w.V, code) / 1e6,
+        "peak_extra_hbm_mb": (flce.flce_rmsnorm_workspace_bytes if args.rmsnorm else
+                              flce.flce_workspace_bytes)(w.BT, w.H, w.V, code) / 1e6,
         "full_logits_avoided_mb": flce.flce_full_logits_bytes(w.BT, w.V, code) / 1e6,
         "loss": float(loss.item()),
         "kernel_ms_per_step": {k: kt[k][0] / args.steps for k in kt},

@@ -234,6 +234,17 @@ struct NormCtx {
     T* dh;           // [BT x H] out
 };
 
+// Which form of the RMSNorm kernels a row length takes: 1, 2 or 4 16-byte vectors per
+// thread (rows of whole vectors, at most 1024 of them, 16-byte aligned operands; the
+// workspace buffers always are), or 0 for the scalar form.
+template <typename T>
+int rmsnorm_vectors_per_thread(int64_t H, const void* x, const void* gamma, const void* dh) {
+    constexpr int N = 16 / (int)sizeof(T);
+    if (H % N != 0 || !aligned(x, 16) || !aligned(gamma, 16) || !aligned(dh, 16)) return 0;
+    const int64_t nvec = H / N;
+    return nvec <= RN_THREADS ? 1 : nvec <= 2 * RN_THREADS ? 2 : nvec <= 4 * RN_THREADS ? 4 : 0;
+}
+
 // One head: count its valid rows, then run the chunk loop.  Gradients are scaled by
 // weight / N_valid.  With dx_add the head's dX is added to what dX already holds
 // (rounded to the storage type once per head), otherwise dX is overwritten.
@@ -291,8 +302,16 @@ int run_head(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t
         }
         if (norm) {   // X holds the raw hidden states: normalise the chunk's rows
             ScopedKernelTimer timer(FLCE_KIND_OTHER, s);
-            hipLaunchKernelGGL((rmsnorm_fwd_kernel<T>), dim3((unsigned)rows), dim3(RN_THREADS), 0, s,
-                               Xin, norm->gamma, norm->eps, (int)H, Xg, norm->rstd, row_map, n_live);
+#define RN_FWD(KERNEL)                                                                           \
+    hipLaunchKernelGGL((KERNEL), dim3((unsigned)rows), dim3(RN_THREADS), 0, s, Xin, norm->gamma, \
+                       norm->eps, (int)H, Xg, norm->rstd, row_map, n_live)
+            switch (rmsnorm_vectors_per_thread<T>(H, Xin, norm->gamma, norm->dh)) {
+                case 1: RN_FWD((rmsnorm_fwd_vec_kernel<T, 1>)); break;
+                case 2: RN_FWD((rmsnorm_fwd_vec_kernel<T, 2>)); break;
+                case 4: RN_FWD((rmsnorm_fwd_vec_kernel<T, 4>)); break;
+                default: RN_FWD((rmsnorm_fwd_kernel<T>)); break;
+            }
+#undef RN_FWD
             HIP_TRY(hipGetLastError());
             Xc = Xg;
         } else if (p.compact) {
@@ -372,10 +391,17 @@ int run_head(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t
             }
             if (norm) {
                 ScopedKernelTimer timer(FLCE_KIND_OTHER, s);
-                hipLaunchKernelGGL((rmsnorm_bwd_kernel<T>), dim3(RN_SLOTS), dim3(RN_THREADS), 0, s, Xin,
-                                   norm->gamma, norm->rstd, dXg, (int)rows, (int)H,
-                                   p.compact ? norm->dh : norm->dh + r0 * H, norm->partial, row_map,
-                                   n_live);
+#define RN_BWD(KERNEL)                                                                              \
+    hipLaunchKernelGGL((KERNEL), dim3(RN_SLOTS), dim3(RN_THREADS), 0, s, Xin, norm->gamma,           \
+                       norm->rstd, dXg, (int)rows, (int)H, p.compact ? norm->dh : norm->dh + r0 * H, \
+                       norm->partial, row_map, n_live)
+                switch (rmsnorm_vectors_per_thread<T>(H, Xin, norm->gamma, norm->dh)) {
+                    case 1: RN_BWD((rmsnorm_bwd_vec_kernel<T, 1>)); break;
+                    case 2: RN_BWD((rmsnorm_bwd_vec_kernel<T, 2>)); break;
+                    case 4: RN_BWD((rmsnorm_bwd_vec_kernel<T, 4>)); break;
+                    default: RN_BWD((rmsnorm_bwd_kernel<T>)); break;
+                }
+#undef RN_BWD
                 HIP_TRY(hipGetLastError());
             } else if (p.compact) {
                 ScopedKernelTimer timer(FLCE_KIND_OTHER, s);

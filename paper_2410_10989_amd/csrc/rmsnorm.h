@@ -11,13 +11,19 @@
 // row p of an fp32 partial buffer [RN_SLOTS x n]; a second kernel adds the
 // partial rows in fixed order.  The kernels are bandwidth bound and touch
 // O(rows * n) bytes, which is negligible next to the three products.
+//
+// Two forms of each kernel: the vector form (rows of up to 4 * 256 16-byte vectors,
+// 16-byte aligned) keeps a row in registers, reads it once with 16-byte accesses and
+// keeps a workgroup's dgamma sums in registers over all its rows; the scalar form
+// takes any row length.
 #pragma once
 #include "flce_device.h"
+#include "rowreduce.h"
 
 namespace flce {
 
 constexpr int RN_THREADS = 256;
-constexpr int RN_SLOTS = 256;
+constexpr int RN_SLOTS = 512;
 
 // Sum over the 256 threads of a workgroup, the same value returned to every thread.
 __device__ __forceinline__ float rn_block_sum(float v, float* red) {
@@ -81,6 +87,117 @@ __global__ __launch_bounds__(RN_THREADS) void rmsnorm_bwd_kernel(
             const float d = to_f32(dy[cbase + j]);
             dx[base + j] = from_f32<T>(r * (d * to_f32(gamma[j]) - dot * xh));
             mine[j] += d * xh;
+        }
+    }
+}
+
+// Vector form of rmsnorm_fwd_kernel: n is a multiple of the vector width, thread t holds
+// vectors t, t + 256, ... (NV of them: n <= NV * 256 vectors).
+template <typename T, int NV>
+__global__ __launch_bounds__(RN_THREADS) void rmsnorm_fwd_vec_kernel(
+    const T* __restrict__ x, const T* __restrict__ gamma, float eps, int n, T* __restrict__ y,
+    float* __restrict__ rstd, const int* __restrict__ idx, const int* __restrict__ live) {
+    constexpr int N = RowVec<T>::N;
+    __shared__ float red[RN_THREADS / WAVE];
+    if (live && (int)blockIdx.x >= *live) return;
+    const int nvec = n / N;
+    const u32x4* xr = reinterpret_cast<const u32x4*>(x + (int64_t)(idx ? idx[blockIdx.x] : (int)blockIdx.x) * n);
+    u32x4* yr = reinterpret_cast<u32x4*>(y + (int64_t)blockIdx.x * n);
+    const u32x4* gr = reinterpret_cast<const u32x4*>(gamma);
+    float xv[NV][N];
+    float ss = 0.f;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        const int v = threadIdx.x + k * RN_THREADS;
+        if (v < nvec) {
+            RowVec<T>::unpack(xr[v], xv[k]);
+#pragma unroll
+            for (int e = 0; e < N; ++e) ss += xv[k][e] * xv[k][e];
+        }
+    }
+    ss = rn_block_sum(ss, red);
+    const float r = 1.0f / sqrtf(ss / (float)n + eps);
+    if (threadIdx.x == 0) rstd[blockIdx.x] = r;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        const int v = threadIdx.x + k * RN_THREADS;
+        if (v < nvec) {
+            float g[N], o[N];
+            RowVec<T>::unpack(gr[v], g);
+#pragma unroll
+            for (int e = 0; e < N; ++e) o[e] = xv[k][e] * r * g[e];
+            yr[v] = RowVec<T>::pack(o);
+        }
+    }
+}
+
+// Vector form of rmsnorm_bwd_kernel (same layout as the forward form): gamma and the
+// workgroup's dgamma sums stay in registers over all its rows; the sums are added to
+// the workgroup's partial row once, at the end.
+template <typename T, int NV>
+__global__ __launch_bounds__(RN_THREADS) void rmsnorm_bwd_vec_kernel(
+    const T* __restrict__ x, const T* __restrict__ gamma, const float* __restrict__ rstd,
+    const T* __restrict__ dy, int rows, int n, T* __restrict__ dx, float* __restrict__ partial,
+    const int* __restrict__ idx, const int* __restrict__ live) {
+    constexpr int N = RowVec<T>::N;
+    __shared__ float red[RN_THREADS / WAVE];
+    const int nvec = n / N;
+    const u32x4* gr = reinterpret_cast<const u32x4*>(gamma);
+    float gv[NV][N], acc[NV][N];
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        const int v = threadIdx.x + k * RN_THREADS;
+#pragma unroll
+        for (int e = 0; e < N; ++e) {
+            gv[k][e] = 0.f;
+            acc[k][e] = 0.f;
+        }
+        if (v < nvec) RowVec<T>::unpack(gr[v], gv[k]);
+    }
+    if (live) rows = min(rows, *live);
+    for (int row = blockIdx.x; row < rows; row += RN_SLOTS) {
+        const int64_t base = (int64_t)(idx ? idx[row] : row) * n;
+        const u32x4* xr = reinterpret_cast<const u32x4*>(x + base);
+        const u32x4* dr = reinterpret_cast<const u32x4*>(dy + (int64_t)row * n);
+        u32x4* outr = reinterpret_cast<u32x4*>(dx + base);
+        const float r = rstd[row];
+        float xh[NV][N], d[NV][N];
+        float dot = 0.f;
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            const int v = threadIdx.x + k * RN_THREADS;
+            if (v < nvec) {
+                RowVec<T>::unpack(xr[v], xh[k]);
+                RowVec<T>::unpack(dr[v], d[k]);
+#pragma unroll
+                for (int e = 0; e < N; ++e) {
+                    xh[k][e] *= r;
+                    dot += xh[k][e] * (d[k][e] * gv[k][e]);
+                }
+            }
+        }
+        dot = rn_block_sum(dot, red) / (float)n;
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+            const int v = threadIdx.x + k * RN_THREADS;
+            if (v < nvec) {
+                float o[N];
+#pragma unroll
+                for (int e = 0; e < N; ++e) {
+                    o[e] = r * (d[k][e] * gv[k][e] - dot * xh[k][e]);
+                    acc[k][e] += d[k][e] * xh[k][e];
+                }
+                outr[v] = RowVec<T>::pack(o);
+            }
+        }
+    }
+    float* mine = partial + (int64_t)blockIdx.x * n;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        const int v = threadIdx.x + k * RN_THREADS;
+        if (v < nvec) {
+#pragma unroll
+            for (int e = 0; e < N; ++e) mine[v * N + e] += acc[k][e];
         }
     }
 }

@@ -57,6 +57,8 @@ def check(w, h, gamma, eps=1e-6, flags=0):
     (300, 136, 1000),    # guarded kernels, ragged
     (77, 100, 333),      # H not a multiple of anything useful
     (600, 1024, 512),    # more rows than backward workgroups: several rows per partial-sum slot
+    (520, 2560, 256),    # two (bf16) or four (fp32) 16-byte vectors per thread in the row kernels
+    (300, 4104, 128),    # four vectors per thread, last one partly used (bf16); scalar form (fp32)
 ])
 def test_rmsnorm_head_matches_oracle(dtype, BT, H, V):
     check(*make_case(BT, H, V, dtype, seed=500 + BT + H))
