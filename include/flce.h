@@ -253,7 +253,8 @@ FLCE_API int flce_timing_collect(double* total_ms, int64_t* launches);
  * B ~ N(0, std_b^2), rounded to bf16.  Work: workgroups * 4 * iters * 16 * 32768
  * flops.  The sustained rate depends on the pattern because the chip lowers its
  * clock as more operand bits toggle; pattern 2 is the ceiling for products of such
- * data.  FLCE_ERR_ARG for sizes out of range (iters <= 2^24, workgroups <= 65536). */
+ * data.  FLCE_ERR_ARG for sizes out of range: workgroups <= 65536 and workgroups *
+ * iters <= 2^26, which bounds a launch to about 0.1 s. */
 FLCE_API int flce_mfma_ceiling_launch(int pattern, int workgroups, int iters, float std_b, float* out,
                                       size_t out_floats, void* stream);
 

@@ -747,7 +747,8 @@ int flce_mfma_ceiling_launch(int pattern, int workgroups, int iters, float std_b
                              size_t out_floats, void* stream) {
     if (!out) return FLCE_ERR_NULL;
     if (pattern < 0 || pattern > 2 || workgroups <= 0 || workgroups > 65536 || iters <= 0 ||
-        iters > (1 << 24) || !(std_b >= 0.0f) || out_floats < (size_t)workgroups * 256)
+        (int64_t)workgroups * iters > ((int64_t)1 << 26) || !(std_b >= 0.0f) ||
+        out_floats < (size_t)workgroups * 256)
         return FLCE_ERR_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid((unsigned)workgroups), block(256);

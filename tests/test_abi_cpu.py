@@ -136,7 +136,7 @@ def test_bad_arguments_are_rejected_on_the_host():
     # the MFMA-only measurement loop
     assert L.flce_mfma_ceiling_launch(2, 256, 100, cf(0.02), None, 65536, None) == 1
     for bad in [(3, 256, 100, 65536), (2, 0, 100, 65536), (2, 256, 0, 65536), (2, 256, 100, 65535),
-                (2, 70000, 100, 1 << 30), (2, 256, (1 << 24) + 1, 65536)]:
+                (2, 70000, 100, 1 << 30), (2, 256, (1 << 18) + 1, 65536)]:
         assert L.flce_mfma_ceiling_launch(bad[0], bad[1], bad[2], cf(0.02), a, bad[3], None) == 7
     assert L.flce_mfma_ceiling_launch(2, 256, 100, cf(float("nan")), a, 65536, None) == 7
     for s in range(8):
