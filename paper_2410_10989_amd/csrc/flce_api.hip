@@ -234,6 +234,26 @@ struct NormCtx {
     T* dh;           // [BT x H] out
 };
 
+// Sum of the K-range partial results of a dX product into dXc (+= with add).
+template <typename T>
+int launch_splitk_reduce(const float* part, int64_t split_stride, int nsplit, T* out, int64_t n,
+                         bool add, hipStream_t s) {
+    ScopedKernelTimer timer(FLCE_KIND_DX_GEMM, s);
+    const bool vec = (n % 4 == 0) && (split_stride % 4 == 0) && aligned(part, 16) &&
+                     aligned(out, 4 * sizeof(T));
+    const dim3 grid(2048), block(256);
+#define SK_LAUNCH(ADD, VEC) \
+    hipLaunchKernelGGL((splitk_reduce_kernel<T, ADD, VEC>), grid, block, 0, s, part, split_stride, nsplit, out, n)
+    if (vec) {
+        if (add) SK_LAUNCH(true, true); else SK_LAUNCH(false, true);
+    } else {
+        if (add) SK_LAUNCH(true, false); else SK_LAUNCH(false, false);
+    }
+#undef SK_LAUNCH
+    HIP_TRY(hipGetLastError());
+    return FLCE_OK;
+}
+
 // Which form of the RMSNorm kernels a row length takes: 1, 2 or 4 16-byte vectors per
 // thread (rows of whole vectors, at most 1024 of them, 16-byte aligned operands; the
 // workspace buffers always are), or 0 for the scalar form.
@@ -353,14 +373,8 @@ int run_head(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t
                         FLCE_TRY((launch_gemm_fast<float, void, false, true>(
                             FLCE_KIND_DX_GEMM, Z, p.ldz, W, H, part, H, nullptr, 0, rows, H, V, s,
                             p.dx_ksplit, p.C * H, n_live, 0)));
-                        ScopedKernelTimer timer(FLCE_KIND_DX_GEMM, s);
-                        if (add_in_gemm)
-                            hipLaunchKernelGGL((splitk_reduce_kernel<bf16_t, true>), dim3(1024), dim3(256),
-                                               0, s, part, p.C * H, p.dx_ksplit, dXc, rows * H);
-                        else
-                            hipLaunchKernelGGL((splitk_reduce_kernel<bf16_t, false>), dim3(1024), dim3(256),
-                                               0, s, part, p.C * H, p.dx_ksplit, dXc, rows * H);
-                        HIP_TRY(hipGetLastError());
+                        FLCE_TRY(launch_splitk_reduce<bf16_t>(part, p.C * H, p.dx_ksplit, dXc, rows * H,
+                                                              add_in_gemm, s));
                     } else if (add_in_gemm) {
                         FLCE_TRY((launch_gemm_fast<bf16_t, bf16_t, false, true>(
                             FLCE_KIND_DX_GEMM, Z, p.ldz, W, H, dXc, H, dXc, H, rows, H, V, s)));
@@ -376,14 +390,8 @@ int run_head(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t
                     FLCE_TRY((launch_gemm_generic<T, float>(FLCE_KIND_DX_GEMM, Z, p.ldz, WT, p.ldz, part,
                                                             H, rows, H, V, false, s, p.dx_ksplit,
                                                             p.C * H)));
-                    ScopedKernelTimer timer(FLCE_KIND_DX_GEMM, s);
-                    if (add_in_gemm)
-                        hipLaunchKernelGGL((splitk_reduce_kernel<T, true>), dim3(1024), dim3(256), 0, s,
-                                           part, p.C * H, p.dx_ksplit, dXc, rows * H);
-                    else
-                        hipLaunchKernelGGL((splitk_reduce_kernel<T, false>), dim3(1024), dim3(256), 0, s,
-                                           part, p.C * H, p.dx_ksplit, dXc, rows * H);
-                    HIP_TRY(hipGetLastError());
+                    FLCE_TRY(launch_splitk_reduce<T>(part, p.C * H, p.dx_ksplit, dXc, rows * H, add_in_gemm,
+                                                     s));
                 } else {
                     FLCE_TRY((launch_gemm_generic<T, T>(FLCE_KIND_DX_GEMM, Z, p.ldz, WT, p.ldz, dXc, H,
                                                         rows, H, V, add_in_gemm, s)));
@@ -525,8 +533,8 @@ int run_rmsnorm_head(const T* h, const T* gamma, float eps, const T* W, const in
     FLCE_TRY(run_head<T>(h, W, targets, BT, H, V, ignore_index, 1.0f, hdr, false, nullptr, dW, flags, p,
                          ws, s, &n));
     if (want_dx) {
-        hipLaunchKernelGGL((rmsnorm_dgamma_kernel<T>), dim3((unsigned)((H + 255) / 256)), dim3(256), 0,
-                           s, n.partial, (int)H, dgamma);
+        hipLaunchKernelGGL((rmsnorm_dgamma_kernel<T>), dim3((unsigned)((H + RN_DG_COLS - 1) / RN_DG_COLS)),
+                           dim3(RN_DG_COLS * RN_DG_PARTS), 0, s, n.partial, (int)H, dgamma);
         HIP_TRY(hipGetLastError());
     }
     HeadWeights one{};

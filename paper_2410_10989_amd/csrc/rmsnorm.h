@@ -208,15 +208,22 @@ __global__ void fill_zero_kernel(float* __restrict__ p, int64_t count) {
         p[i] = 0.f;
 }
 
-// dgamma[j] = sum_p partial[p][j], p = 0, 1, ... in order.
+// dgamma[j] = sum_p partial[p][j].  A workgroup of 64 x 4 threads owns 64 columns: thread
+// (c, q) adds rows q, q + 4, ... of column c in order, then the four sums are added in
+// the order q = 0, 1, 2, 3: a fixed order, and 4 n / 256 workgroups instead of n / 256.
+constexpr int RN_DG_COLS = 64, RN_DG_PARTS = 4;
 template <typename T>
-__global__ void rmsnorm_dgamma_kernel(const float* __restrict__ partial, int n,
-                                      T* __restrict__ dgamma) {
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= n) return;
+__global__ __launch_bounds__(RN_DG_COLS * RN_DG_PARTS) void rmsnorm_dgamma_kernel(
+    const float* __restrict__ partial, int n, T* __restrict__ dgamma) {
+    __shared__ float sums[RN_DG_PARTS][RN_DG_COLS];
+    const int c = threadIdx.x % RN_DG_COLS, q = threadIdx.x / RN_DG_COLS;
+    const int j = blockIdx.x * RN_DG_COLS + c;
     float s = 0.f;
-    for (int p = 0; p < RN_SLOTS; ++p) s += partial[(int64_t)p * n + j];
-    dgamma[j] = from_f32<T>(s);
+    if (j < n)
+        for (int p = q; p < RN_SLOTS; p += RN_DG_PARTS) s += partial[(int64_t)p * n + j];
+    sums[q][c] = s;
+    __syncthreads();
+    if (q == 0 && j < n) dgamma[j] = from_f32<T>(((sums[0][c] + sums[1][c]) + sums[2][c]) + sums[3][c]);
 }
 
 }  // namespace flce
