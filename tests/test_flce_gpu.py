@@ -49,6 +49,7 @@ def test_config1_tiny_fp32():
     (520, 256, 3001, ("iid", 0.1)),     # tuned kernels with V % 64 != 0: zero-padded K tail of dX
     (1000, 128, 50257 // 8, ("iid", 0.1)),   # odd V (a GPT-2 style vocabulary, scaled down) and rows % 64 != 0
     (70, 64, 65, ("none",)),            # one column past a K step; fewer rows than a K step
+    (640, 1032, 4096, ("iid", 0.1)),    # guarded kernels over many tiles and K steps in every product
     (5, 8, 1, ("none",)),               # one class: the loss and every gradient are exactly zero
     (9, 1, 5, ("iid", 0.2)),            # hidden size one
 ])
