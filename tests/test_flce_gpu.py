@@ -12,6 +12,11 @@ from oracle import flce_oracle as oracle
 pytestmark = pytest.mark.gpu
 
 
+def to_device_like(ref: torch.Tensor, a: np.ndarray) -> torch.Tensor:
+    from flce_testlib import to_device
+    return to_device(a, "bf16" if ref.dtype == torch.bfloat16 else "f32")
+
+
 def check_full(w, flags=0):
     import paper_2410_10989_amd as flce
     print(f"case {w.name} BT={w.BT} H={w.H} V={w.V} {w.dtype} seed={w.seed} flags={flags} "
@@ -248,6 +253,59 @@ def test_call_can_be_captured_in_a_graph_and_replayed():
             assert got[0] == e_loss.item()
             assert torch.equal(got[1].view(torch.int16), e_dX.view(torch.int16))
             assert torch.equal(got[2].view(torch.int16), e_dW.view(torch.int16))
+    finally:
+        flce.flce_set_logits_budget_bytes(old)
+
+
+def test_multihead_and_rmsnorm_entries_can_be_captured_too():
+    # same property for the other two entry points (dX accumulated over heads; dgamma partial
+    # sums cleared by a kernel inside the call): replays equal the eager results bit for bit
+    import paper_2410_10989_amd as flce
+    m = workloads.make_multihead(2, 513, 192, 1536, 64, "bf16", ignore=("iid", 0.1), seed=29)
+    X0, W0, t0 = upload(m.base)
+    Ws = [W0] + [to_device_like(W0, m.Ws[1])]
+    ts = [torch.from_numpy(t).cuda() for t in m.targets]
+    h_np, gamma_np = workloads.make_rmsnorm_inputs(m.base)
+    gamma = to_device_like(W0, gamma_np)
+    old = flce.flce_get_logits_budget_bytes()
+    try:
+        flce.flce_set_logits_budget_bytes(256 * 1536 * 2)
+        X = X0.clone()
+        loss, loss_n = (torch.empty((), dtype=torch.float32, device="cuda") for _ in range(2))
+        hl = torch.empty(2, dtype=torch.float32, device="cuda")
+        dX, dh = torch.empty_like(X), torch.empty_like(X)
+        dWs = [torch.empty_like(W0) for _ in range(2)]
+        dWn, dgamma = torch.empty_like(W0), torch.empty_like(gamma)
+
+        def heads(loss, hl, dX, dWs):
+            return flce.flce_multihead_fwd_bwd(X, Ws, ts, list(m.weights), m.base.ignore_index, loss=loss,
+                                               head_losses=hl, dX=dX, dWs=dWs)
+
+        def norm(loss, dh, dgamma, dW):
+            return flce.flce_rmsnorm_fwd_bwd(X, gamma, 1e-6, W0, ts[0], m.base.ignore_index, loss=loss,
+                                             dh=dh, dgamma=dgamma, dW=dW)
+
+        heads(loss, hl, dX, dWs)            # size the workspaces
+        norm(loss_n, dh, dgamma, dWn)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            heads(loss, hl, dX, dWs)
+            norm(loss_n, dh, dgamma, dWn)
+        for scale in (1.0, -0.5, 1.0):
+            X.copy_(X0 * scale)
+            for b in (dX, dh, dWn, dgamma, *dWs):
+                b.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            got = [x.clone() for x in (loss, hl, dX, *dWs, loss_n, dh, dgamma, dWn)]
+            e_hl = torch.empty_like(hl)
+            e = heads(torch.empty_like(loss), e_hl, torch.empty_like(dX), [torch.empty_like(W0) for _ in range(2)])
+            n = norm(torch.empty_like(loss), torch.empty_like(dh), torch.empty_like(dgamma), torch.empty_like(W0))
+            torch.cuda.synchronize()
+            want = [e[0], e_hl, e[2], *e[3], n[0], n[1], n[2], n[3]]
+            for a, b in zip(got, want):
+                assert torch.equal(a.reshape(-1).view(torch.uint8), b.reshape(-1).view(torch.uint8))
     finally:
         flce.flce_set_logits_budget_bytes(old)
 
