@@ -75,7 +75,8 @@ typedef enum {
     FLCE_ERR_ALIGN = 4,     /* a pointer misses its alignment                 */
     FLCE_ERR_WORKSPACE = 5, /* lent workspace too small, or allocation failed */
     FLCE_ERR_HIP = 6,       /* a HIP runtime call or kernel launch failed     */
-    FLCE_ERR_ARG = 7        /* any other invalid argument                     */
+    FLCE_ERR_ARG = 7,       /* any other invalid argument                     */
+    FLCE_ERR_TOO_LARGE = 8  /* more rows than an allocation-free entry point's fixed scratch holds */
 } flce_status;
 
 /* Flags for flce_fwd_bwd_ex: skip one of the two gradients (a frozen backbone
@@ -171,6 +172,26 @@ FLCE_API size_t flce_rmsnorm_workspace_bytes(int64_t BT, int64_t H, int64_t V, i
 FLCE_API int flce_cross_entropy_inplace(void* Z, const int64_t* targets, int64_t BT, int64_t V,
                                int64_t ldz, int64_t ignore_index, int dtype, float* loss,
                                void* stream);
+
+/*
+ * flce_cross_entropy_inplace for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same kernels, same results bit for bit, but the device header and
+ * the per-row losses live in a fixed array inside the library's device image
+ * (256 + 4 * FLCE_CE_NOALLOC_MAX_ROWS bytes = 262 400 bytes on every GPU the library
+ * is used on, held until the process ends) instead of the workspace, so the call
+ * allocates and frees nothing and ignores flce_set_workspace and flce_timing_enable.
+ *   BT > FLCE_CE_NOALLOC_MAX_ROWS returns FLCE_ERR_TOO_LARGE before anything is launched.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU
+ * (different streams, different threads) race; serialise them on one stream.  The
+ * array keeps the previous call's contents; the kernels overwrite every slot they
+ * read, nothing needs clearing.  The first call on a device looks the array's device
+ * address up (hipGetSymbolAddress): make one call outside stream capture first.
+ */
+#define FLCE_CE_NOALLOC_MAX_ROWS 65536
+FLCE_API int flce_cross_entropy_inplace_noalloc(void* Z, const int64_t* targets, int64_t BT, int64_t V,
+                                       int64_t ldz, int64_t ignore_index, int dtype, float* loss,
+                                       void* stream);
 
 /* Bytes of device scratch flce_fwd_bwd uses for this problem.  For fixed H, V
  * and dtype it does not grow with BT once BT exceeds one chunk:

@@ -41,6 +41,7 @@ def lib() -> ctypes.CDLL:
             "flce_rmsnorm_fwd_bwd": ([p, p, ctypes.c_float, p, p, i64, i64, i64, i64, ci, p, p, p, p, u, p], ci),
             "flce_rmsnorm_workspace_bytes": ([i64, i64, i64, ci], sz),
             "flce_cross_entropy_inplace": ([p, p, i64, i64, i64, i64, ci, p, p], ci),
+            "flce_cross_entropy_inplace_noalloc": ([p, p, i64, i64, i64, i64, ci, p, p], ci),
             "flce_workspace_bytes": ([i64, i64, i64, ci], sz),
             "flce_workspace_bytes_max": ([i64, i64, ci], sz),
             "flce_set_workspace": ([p, sz], ci),
@@ -219,8 +220,13 @@ def flce_rmsnorm_workspace_bytes(BT, H, V, dtype) -> int:
     return int(lib().flce_rmsnorm_workspace_bytes(BT, H, V, _DTYPES.get(dtype, dtype)))
 
 
-def flce_cross_entropy_inplace(Z, targets, ignore_index=-100, loss=None, stream=None):
-    """Replaces logits Z [BT, V] (row stride Z.stride(0)) by dL/dZ; returns the mean loss."""
+CE_NOALLOC_MAX_ROWS = 65536
+
+
+def flce_cross_entropy_inplace(Z, targets, ignore_index=-100, loss=None, stream=None, noalloc=False):
+    """Replaces logits Z [BT, V] (row stride Z.stride(0)) by dL/dZ; returns the mean loss.
+    noalloc=True calls flce_cross_entropy_inplace_noalloc (pass `loss`: this wrapper
+    would otherwise allocate it)."""
     code = _dtype_code(Z)
     if Z.dim() != 2 or Z.stride(1) != 1 or targets.shape != (Z.shape[0],):
         raise ValueError("expected Z [BT, V] with unit column stride, targets [BT]")
@@ -230,12 +236,16 @@ def flce_cross_entropy_inplace(Z, targets, ignore_index=-100, loss=None, stream=
     if loss is None:
         loss = torch.empty((), dtype=torch.float32, device=Z.device)
     with torch.cuda.device(Z.device):
-        st = lib().flce_cross_entropy_inplace(Z.data_ptr(), _dev_ptr(targets, "targets"), BT, V,
-                                              Z.stride(0) if BT > 1 else max(V, Z.stride(0)),
-                                              int(ignore_index), code, _dev_ptr(loss, "loss"),
-                                              _stream_handle(stream))
-    _check(st, "flce_cross_entropy_inplace")
+        fn = lib().flce_cross_entropy_inplace_noalloc if noalloc else lib().flce_cross_entropy_inplace
+        st = fn(Z.data_ptr(), _dev_ptr(targets, "targets"), BT, V,
+                Z.stride(0) if BT > 1 else max(V, Z.stride(0)), int(ignore_index), code,
+                _dev_ptr(loss, "loss"), _stream_handle(stream))
+    _check(st, "flce_cross_entropy_inplace_noalloc" if noalloc else "flce_cross_entropy_inplace")
     return loss
+
+
+def flce_cross_entropy_inplace_noalloc(Z, targets, ignore_index=-100, loss=None, stream=None):
+    return flce_cross_entropy_inplace(Z, targets, ignore_index, loss, stream, noalloc=True)
 
 
 def flce_workspace_bytes(BT, H, V, dtype) -> int:

@@ -18,6 +18,13 @@
 
 using namespace flce;
 
+// Scratch of flce_cross_entropy_inplace_noalloc: the device header and one loss per
+// row, in the image of the code object instead of allocated memory.  Every GPU the
+// library runs on holds its own copy at its own address until the process ends.  In
+// host code this name is only a handle for hipGetSymbolAddress, never an address.
+constexpr size_t CE_NOALLOC_BYTES = 256 + (size_t)FLCE_CE_NOALLOC_MAX_ROWS * sizeof(float);
+static __device__ __align__(256) unsigned char scratch[CE_NOALLOC_BYTES];
+
 namespace {
 
 constexpr int MAX_DEVICES = 64;
@@ -35,6 +42,7 @@ struct DeviceWorkspace {
 
 std::mutex g_mutex;
 DeviceWorkspace g_ws[MAX_DEVICES];
+void* g_scratch_ptr[MAX_DEVICES] = {};   // device address of `scratch` on each device, once looked up
 size_t g_budget = 0;   // 0 = the automatic rule of effective_budget()
 bool g_compact = true;
 
@@ -61,8 +69,8 @@ struct ScopedKernelTimer {
     hipStream_t stream;
     bool active = false;
     TimingRecord rec{};
-    ScopedKernelTimer(int kind, hipStream_t s) : stream(s) {
-        if (!g_timing_on || (int)g_records.size() >= MAX_TIMING_RECORDS) return;
+    ScopedKernelTimer(int kind, hipStream_t s) : stream(s) {   // kind < 0: never timed
+        if (kind < 0 || !g_timing_on || (int)g_records.size() >= MAX_TIMING_RECORDS) return;
         if (hipEventCreate(&rec.start) != hipSuccess) return;
         if (hipEventCreate(&rec.stop) != hipSuccess) {
             (void)hipEventDestroy(rec.start);
@@ -186,9 +194,9 @@ int launch_transpose(const T* in, int64_t ldin, T* out, int64_t ldout, int64_t R
 template <typename T>
 int launch_ce_rows(T* Z, int64_t ldz, const int64_t* targets, int64_t rows, int64_t V,
                    int zero_pad, int64_t ignore_index, DeviceHeader* hdr, float* row_loss,
-                   hipStream_t s, const int* n_rows = nullptr) {
+                   hipStream_t s, const int* n_rows = nullptr, bool timed = true) {
     const bool vec = aligned(Z, 16) && ((ldz * sizeof(T)) % 16 == 0);
-    ScopedKernelTimer timer(FLCE_KIND_CE_ROWS, s);
+    ScopedKernelTimer timer(timed ? FLCE_KIND_CE_ROWS : -1, s);
     // rows from 96 KB on: the 1024-thread kernel that keeps the first 256 KB of the row in
     // registers (measured 4.6-5.3 TB/s against 3.4-3.9 for two plain sweeps; below 96 KB
     // the 256-thread kernel's higher occupancy wins)
@@ -545,6 +553,43 @@ int run_rmsnorm_head(const T* h, const T* gamma, float eps, const T* W, const in
     return FLCE_OK;
 }
 
+// Argument checks shared by the two stand-alone cross-entropy entry points.
+int check_ce_args(const void* Z, const int64_t* targets, int64_t BT, int64_t V, int64_t ldz,
+                  int64_t ignore_index, int dtype, const float* loss) {
+    FLCE_TRY(check_dims(BT, 1, V, dtype));
+    if (!Z || !targets || !loss) return FLCE_ERR_NULL;
+    if (ldz < V || ldz > MAX_DIM * 4) return FLCE_ERR_SHAPE;
+    if (!aligned(Z, elem_size(dtype)) || !aligned(targets, 8) || !aligned(loss, 4))
+        return FLCE_ERR_ALIGN;
+    if (ignore_index >= 0 && ignore_index < V) return FLCE_ERR_ARG;
+    return FLCE_OK;
+}
+
+// Stand-alone cross entropy on logits Z, `step` rows per launch, with the device header
+// and the per-row losses (`step` floats) in memory the caller of this function provides.
+int run_ce_inplace(void* Z, const int64_t* targets, int64_t BT, int64_t V, int64_t ldz,
+                   int64_t ignore_index, int dtype, float* loss, DeviceHeader* hdr, float* row_loss,
+                   int64_t step, bool timed, hipStream_t s) {
+    hipLaunchKernelGGL(count_valid_kernel, dim3(1), dim3(1024), 0, s, targets, BT, ignore_index,
+                       1.0f, hdr);
+    HIP_TRY(hipGetLastError());
+    for (int64_t r0 = 0; r0 < BT; r0 += step) {
+        const int64_t rows = (BT - r0 < step) ? BT - r0 : step;
+        if (dtype == FLCE_F32)
+            FLCE_TRY(launch_ce_rows<float>(static_cast<float*>(Z) + r0 * ldz, ldz, targets + r0,
+                                           rows, V, 0, ignore_index, hdr, row_loss, s, nullptr, timed));
+        else
+            FLCE_TRY(launch_ce_rows<bf16_t>(static_cast<bf16_t*>(Z) + r0 * ldz, ldz, targets + r0,
+                                            rows, V, 0, ignore_index, hdr, row_loss, s, nullptr, timed));
+    }
+    HeadWeights one{};
+    one.w[0] = 1.0f;
+    hipLaunchKernelGGL(finalize_loss_kernel, dim3(1), dim3(64), 0, s, hdr, 1, one, loss,
+                       static_cast<float*>(nullptr));
+    HIP_TRY(hipGetLastError());
+    return FLCE_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -642,36 +687,40 @@ int flce_fwd_bwd(const void* X, const void* W, const int64_t* targets, int64_t B
 
 int flce_cross_entropy_inplace(void* Z, const int64_t* targets, int64_t BT, int64_t V, int64_t ldz,
                                int64_t ignore_index, int dtype, float* loss, void* stream) {
-    FLCE_TRY(check_dims(BT, 1, V, dtype));
-    if (!Z || !targets || !loss) return FLCE_ERR_NULL;
-    if (ldz < V || ldz > MAX_DIM * 4) return FLCE_ERR_SHAPE;
-    if (!aligned(Z, elem_size(dtype)) || !aligned(targets, 8) || !aligned(loss, 4))
-        return FLCE_ERR_ALIGN;
-    if (ignore_index >= 0 && ignore_index < V) return FLCE_ERR_ARG;
+    FLCE_TRY(check_ce_args(Z, targets, BT, V, ldz, ignore_index, dtype, loss));
     const int64_t step = BT < CE_ROWS_PER_LAUNCH ? BT : CE_ROWS_PER_LAUNCH;
     char* ws = nullptr;
     FLCE_TRY(acquire_workspace(256 + (size_t)step * sizeof(float), &ws));
-    DeviceHeader* hdr = reinterpret_cast<DeviceHeader*>(ws);
-    float* row_loss = reinterpret_cast<float*>(ws + 256);
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipLaunchKernelGGL(count_valid_kernel, dim3(1), dim3(1024), 0, s, targets, BT, ignore_index,
-                       1.0f, hdr);
-    HIP_TRY(hipGetLastError());
-    for (int64_t r0 = 0; r0 < BT; r0 += step) {
-        const int64_t rows = (BT - r0 < step) ? BT - r0 : step;
-        if (dtype == FLCE_F32)
-            FLCE_TRY(launch_ce_rows<float>(static_cast<float*>(Z) + r0 * ldz, ldz, targets + r0,
-                                           rows, V, 0, ignore_index, hdr, row_loss, s));
-        else
-            FLCE_TRY(launch_ce_rows<bf16_t>(static_cast<bf16_t*>(Z) + r0 * ldz, ldz, targets + r0,
-                                            rows, V, 0, ignore_index, hdr, row_loss, s));
+    return run_ce_inplace(Z, targets, BT, V, ldz, ignore_index, dtype, loss,
+                          reinterpret_cast<DeviceHeader*>(ws), reinterpret_cast<float*>(ws + 256), step,
+                          true, static_cast<hipStream_t>(stream));
+}
+
+int flce_cross_entropy_inplace_noalloc(void* Z, const int64_t* targets, int64_t BT, int64_t V,
+                                       int64_t ldz, int64_t ignore_index, int dtype, float* loss,
+                                       void* stream) {
+    FLCE_TRY(check_ce_args(Z, targets, BT, V, ldz, ignore_index, dtype, loss));
+    if (BT > FLCE_CE_NOALLOC_MAX_ROWS) return FLCE_ERR_TOO_LARGE;
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return FLCE_ERR_ARG;
+    char* ptr = nullptr;
+    {
+        // first call on this device: ask the runtime where this device's copy of the array is
+        std::lock_guard<std::mutex> lock(g_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void* p = nullptr;
+            HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+            if (!p) return FLCE_ERR_HIP;
+            g_scratch_ptr[dev] = p;
+        }
+        ptr = static_cast<char*>(g_scratch_ptr[dev]);
     }
-    HeadWeights one{};
-    one.w[0] = 1.0f;
-    hipLaunchKernelGGL(finalize_loss_kernel, dim3(1), dim3(64), 0, s, hdr, 1, one, loss,
-                       static_cast<float*>(nullptr));
-    HIP_TRY(hipGetLastError());
-    return FLCE_OK;
+    // The header is reset by the counting kernel and every row's loss slot is written by the
+    // row kernel before it is summed, so nothing of the previous call's contents is read.
+    return run_ce_inplace(Z, targets, BT, V, ldz, ignore_index, dtype, loss,
+                          reinterpret_cast<DeviceHeader*>(ptr), reinterpret_cast<float*>(ptr + 256), BT,
+                          false, static_cast<hipStream_t>(stream));
 }
 
 size_t flce_workspace_bytes(int64_t BT, int64_t H, int64_t V, int dtype) {
@@ -808,6 +857,7 @@ const char* flce_status_string(int status) {
         case FLCE_ERR_WORKSPACE: return "workspace too small or allocation failed";
         case FLCE_ERR_HIP: return "a HIP runtime call or kernel launch failed";
         case FLCE_ERR_ARG: return "invalid argument";
+        case FLCE_ERR_TOO_LARGE: return "problem larger than the fixed scratch of the allocation-free entry point";
         default: return "unknown status";
     }
 }
