@@ -19,9 +19,11 @@
 //                                                    2-3 and the sum over rows)
 // Chunking only reorders the sum over rows, so the oracle is the unfused
 // definition.  Rows are visited in blocks solely to bound the RAM held by the
-// logits; every logit is one plain dot product and every sum runs in index
-// order.  N = 0 gives loss = 0 and zero gradients (a reading: the paper does
-// not cover it).  "Safe log": log is only ever taken of sum exp(z - max) >= 1.
+// logits; every logit is one plain dot product.  The dot products carry
+// `omp simd reduction`, so the compiler may keep one partial sum per vector lane
+// and add the lanes at the end (a different association of the same fp64 sum, a
+// few 1e-16 relative); all other sums run in index order.  N = 0 gives loss = 0
+// and zero gradients (a reading: the paper does not cover it).  "Safe log": log is only ever taken of sum exp(z - max) >= 1.
 //
 // Optional row / vocabulary selections return dX only for the listed rows and
 // dW only for the listed vocabulary ids; the arithmetic per returned element is

@@ -27,10 +27,12 @@ class FlceError(RuntimeError):
 
 
 def lib() -> ctypes.CDLL:
-    """Loads libflce.so (building it first only if no built library exists)."""
+    """Loads libflce.so, building it first when there is none or when a kernel source or
+    the header is newer than the built library (so an edited kernel is never tested
+    against an old binary)."""
     global _lib
     if _lib is None:
-        if not os.path.exists(_build.LIB_PATH):
+        if _build.is_stale():
             _build.build()
         L = ctypes.CDLL(_build.LIB_PATH)
         p, i64, sz, ci, u = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t, ctypes.c_int, ctypes.c_uint
