@@ -11,6 +11,7 @@
 // without compaction; only dW sums the same non-zero terms in other groups of K.
 #pragma once
 #include "flce_device.h"
+#include "scheduler.h"
 
 namespace flce {
 
@@ -22,23 +23,44 @@ __device__ __forceinline__ int dyn_live_rows(const int* live, int sub, int cap) 
     return min(cap, max(0, *live - sub));
 }
 
-// One workgroup.  Collects the next valid rows of the batch, at most `cap`, starting at
-// the row cursor dyn[0] (at row 0 when `first`):
+// Words of the device array that carries the chunk loop's state from kernel to kernel.
+enum { DYN_CURSOR = 0,      // first batch row the next chunk looks at
+       DYN_LIVE = 1,        // rows of the current chunk
+       DYN_FIRST_LIVE = 2,  // index of the first chunk launch that holds rows
+       DYN_DX_RANGES = 3 }; // K ranges of the current chunk's dX product
+
+// One workgroup; launch `c` of `nchunks`, each sized for `C` rows.  The N valid rows of
+// the batch (N = hdr->n_valid, counted before the loop) are dealt evenly to the LAST
+// n = max(1, ceil(N / C)) launches, ceil_256(ceil(N / n)) rows each (the last one takes
+// what is left), so no launch ends up with a handful of rows and a batch with many
+// ignored rows runs fewer chunks: launches before the first live one hold no rows, and
+// the dW product, which keeps fp32 partial sums from the first live chunk to the last
+// launch, skips them altogether.  The last launch is always live (with N = 0 it holds
+// zero rows and writes a zero dW).  For a live launch this collects the next valid rows
+// of the batch starting at the row cursor:
 //   idx[i] = row of the i-th collected row (ascending), tv[i] = its target
-//   dyn[1] = number of rows collected, dyn[0] = the row after the last one looked at
+//   dyn[DYN_LIVE] = rows collected, dyn[DYN_CURSOR] = the row after the last one looked at
+//   dyn[DYN_DX_RANGES] = K ranges of the dX product for that many rows (dx_tiles_n tile
+//   columns, dx_ksteps K steps, at most dx_max_ranges ranges)
 __global__ __launch_bounds__(CP_THREADS) void compact_chunk_kernel(
-    const int64_t* __restrict__ targets, int BT, int64_t ignore_index, int cap, int first,
+    const int64_t* __restrict__ targets, int BT, int64_t ignore_index, int C, int c, int nchunks,
+    const DeviceHeader* __restrict__ hdr, int dx_tiles_n, int dx_ksteps, int dx_max_ranges,
     int* __restrict__ idx, int64_t* __restrict__ tv, int* __restrict__ dyn) {
     __shared__ int wave_total[CP_THREADS / WAVE];
     __shared__ int s_next;
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
-    int cursor = first ? 0 : dyn[0];
+    const int n_valid = hdr->n_valid;
+    const int n_live = max(1, (n_valid + C - 1) / C);
+    const int first_live = nchunks - n_live;
+    const int quota = min(C, ((n_valid + n_live - 1) / n_live + 255) / 256 * 256);
+    const int cap = c < first_live ? 0 : quota;
+    int cursor = c == 0 ? 0 : dyn[DYN_CURSOR];
     int found = 0;
     while (cursor < BT && found < cap) {   // uniform: every thread sees the same values
         const int r0 = min(BT, cursor + tid * CP_PER), r1 = min(BT, r0 + CP_PER);
-        int c = 0;
-        for (int r = r0; r < r1; ++r) c += (targets[r] != ignore_index);
-        int incl = c;   // inclusive prefix sum over the workgroup
+        int n = 0;
+        for (int r = r0; r < r1; ++r) n += (targets[r] != ignore_index);
+        int incl = n;   // inclusive prefix sum over the workgroup
 #pragma unroll
         for (int o = 1; o < WAVE; o <<= 1) {
             const int up = __shfl_up(incl, o, WAVE);
@@ -53,7 +75,7 @@ __global__ __launch_bounds__(CP_THREADS) void compact_chunk_kernel(
             if (w < wave) base += wave_total[w];
             total += wave_total[w];
         }
-        int at = found + base + incl - c;
+        int at = found + base + incl - n;
         for (int r = r0; r < r1; ++r) {
             const int64_t t = targets[r];
             if (t != ignore_index) {
@@ -75,8 +97,11 @@ __global__ __launch_bounds__(CP_THREADS) void compact_chunk_kernel(
         }
     }
     if (tid == 0) {
-        dyn[0] = cursor;
-        dyn[1] = found;
+        dyn[DYN_CURSOR] = cursor;
+        dyn[DYN_LIVE] = found;
+        dyn[DYN_FIRST_LIVE] = first_live;
+        dyn[DYN_DX_RANGES] = dx_max_ranges > 1
+            ? choose_ksplit((int64_t)((found + 255) / 256) * dx_tiles_n, dx_ksteps, dx_max_ranges) : 1;
     }
 }
 

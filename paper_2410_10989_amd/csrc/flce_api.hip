@@ -56,6 +56,21 @@ size_t effective_budget(int64_t V, int dtype) {
     return rows_bytes > AUTO_BUDGET_BYTES ? rows_bytes : AUTO_BUDGET_BYTES;
 }
 
+// Up to how many bytes of logits a batch runs as ONE chunk.  With an explicit budget:
+// the budget.  Automatic rule: the chunk budget plus the fp32 dW partial sums that only
+// a chunked run needs (bf16 storage), i.e. one chunk whenever that takes no more memory
+// than chunking would; it is also the faster plan.
+size_t single_chunk_bytes(int64_t H, int64_t V, int dtype) {
+    const size_t b = effective_budget(V, dtype);
+    if (g_budget || dtype == FLCE_F32) return b;
+    return b + (size_t)V * (size_t)H * sizeof(float);
+}
+
+Plan plan_for(int64_t BT, int64_t H, int64_t V, int dtype, bool worst_case_bt = false) {
+    return make_plan(BT, H, V, dtype, effective_budget(V, dtype), worst_case_bt, g_compact,
+                     single_chunk_bytes(H, V, dtype));
+}
+
 // ---- optional per-kernel timing (benchmarks only) ----
 struct TimingRecord {
     hipEvent_t start, stop;
@@ -156,19 +171,27 @@ int launch_gemm_generic(int kind, const T* A, int64_t lda, const T* B, int64_t l
     return FLCE_OK;
 }
 
+// What only the device knows about a product launch of a compacted chunk (see FGArgs).
+struct FastDyn {
+    const int* rows = nullptr;      // live rows: replaces M (is_k = 0) or K (is_k = 1)
+    int is_k = 0;
+    const int* ksplit = nullptr;    // number of K ranges, at most the launch's ksplit
+    const int* first_live = nullptr;
+    int launch = 0;
+};
+
 // Tuned bf16 kernel (see gemm_bf16_nt.h for what A_KM / B_KM / InT mean).  The
 // caller has checked the shape limits (Plan::fast_*).
 template <typename OutT, typename InT, bool A_KM, bool B_KM>
 int launch_gemm_fast(int kind, const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, OutT* C,
                      int64_t ldc, const InT* Cin, int64_t ldcin, int64_t M, int64_t N, int64_t K,
-                     hipStream_t s, int ksplit = 1, int64_t split_stride = 0,
-                     const int* dyn_rows = nullptr, int dyn_is_k = 0) {
+                     hipStream_t s, int ksplit = 1, int64_t split_stride = 0, const FastDyn& d = FastDyn{}) {
     if (M <= 0 || N <= 0 || K <= 0) return FLCE_OK;
     if (!aligned(A, 16) || !aligned(B, 16)) return FLCE_ERR_ARG;
     ScopedKernelTimer timer(kind, s);
     FGArgs a{A, lda, B, ldb, C, ldc, Cin, ldcin, (int)M, (int)N, (int)K,
              (int)((M + FG_BM - 1) / FG_BM), (int)((N + FG_BN - 1) / FG_BN), ksplit, split_stride,
-             dyn_rows, dyn_is_k};
+             d.rows, d.is_k, d.ksplit, d.first_live, d.launch};
     const int64_t total = (int64_t)a.tiles_m * a.tiles_n * ksplit;
     if (total >= ((int64_t)1 << 30)) return FLCE_ERR_SHAPE;   // the kernel counts tiles in 32 bits
     const dim3 grid((unsigned)((total + FG_XCDS - 1) / FG_XCDS * FG_XCDS));
@@ -245,13 +268,13 @@ struct NormCtx {
 // Sum of the K-range partial results of a dX product into dXc (+= with add).
 template <typename T>
 int launch_splitk_reduce(const float* part, int64_t split_stride, int nsplit, T* out, int64_t n,
-                         bool add, hipStream_t s) {
+                         bool add, hipStream_t s, const int* dyn_nsplit = nullptr) {
     ScopedKernelTimer timer(FLCE_KIND_DX_GEMM, s);
     const bool vec = (n % 4 == 0) && (split_stride % 4 == 0) && aligned(part, 16) &&
                      aligned(out, 4 * sizeof(T));
     const dim3 grid(2048), block(256);
 #define SK_LAUNCH(ADD, VEC) \
-    hipLaunchKernelGGL((splitk_reduce_kernel<T, ADD, VEC>), grid, block, 0, s, part, split_stride, nsplit, out, n)
+    hipLaunchKernelGGL((splitk_reduce_kernel<T, ADD, VEC>), grid, block, 0, s, part, split_stride, nsplit, out, n, dyn_nsplit)
     if (vec) {
         if (add) SK_LAUNCH(true, true); else SK_LAUNCH(false, true);
     } else {
@@ -310,23 +333,32 @@ int run_head(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t
     bool dw_needs_cast = false;
     for (int64_t c = 0; c < p.nchunks; ++c) {
         const int64_t r0 = c * p.C;
-        const int64_t rows = (BT - r0 < p.C) ? BT - r0 : p.C;
         const bool last = (c == p.nchunks - 1);
-        // Compacted: the chunk is the next (at most) `rows` rows of the batch that have a
-        // target, wherever they are; Xc, Z and dXc hold *n_live rows (a device value), the
-        // launches below are sized for `rows`, and idx maps the chunk's rows to batch rows.
-        // Otherwise the chunk is rows r0 .. r0 + rows - 1 of the batch.
-        const int* n_live = p.compact ? dyn + 1 : nullptr;
+        // Compacted: the chunk is the next rows of the batch that have a target, wherever they
+        // are, at most C of them (the valid rows are dealt evenly to the last launches, see
+        // compact_chunk_kernel); Xc, Z and dXc hold *n_live rows (a device value), the launches
+        // below are sized for C rows, and idx maps the chunk's rows to batch rows.  Otherwise
+        // the chunk is rows r0 .. r0 + rows - 1 of the batch.
+        const int64_t rows = p.compact ? p.C : ((BT - r0 < p.C) ? BT - r0 : p.C);
+        const int* n_live = p.compact ? dyn + DYN_LIVE : nullptr;
         const int* row_map = p.compact ? idx : nullptr;
         const T* Xin = p.compact ? X : X + r0 * H;   // what the chunk's row indices refer to
         const T* Xc = Xin;
         const int64_t* tc = targets + r0;
+        FastDyn dyn_m, dyn_dx, dyn_dw;   // logits (M = live rows), dX (M and K ranges), dW (K = live rows)
         if (p.compact) {
             ScopedKernelTimer timer(FLCE_KIND_OTHER, s);
             hipLaunchKernelGGL(compact_chunk_kernel, dim3(1), dim3(CP_THREADS), 0, s, targets, (int)BT,
-                               ignore_index, (int)rows, c == 0 ? 1 : 0, idx, tv, dyn);
+                               ignore_index, (int)p.C, (int)c, (int)p.nchunks, hdr,
+                               (int)((H + FG_BN - 1) / FG_BN), (int)((V + FG_BK - 1) / FG_BK),
+                               p.dx_ksplit, idx, tv, dyn);
             HIP_TRY(hipGetLastError());
             tc = tv;
+            dyn_m.rows = dyn_dx.rows = dyn_dw.rows = n_live;
+            dyn_dw.is_k = 1;
+            dyn_dx.ksplit = dyn + DYN_DX_RANGES;
+            dyn_dw.first_live = dyn + DYN_FIRST_LIVE;
+            dyn_dw.launch = (int)c;
         }
         if (norm) {   // X holds the raw hidden states: normalise the chunk's rows
             ScopedKernelTimer timer(FLCE_KIND_OTHER, s);
@@ -355,8 +387,7 @@ int run_head(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t
         if (BF16 && p.fast_logits) {
             if constexpr (BF16)
                 FLCE_TRY((launch_gemm_fast<bf16_t, void, false, false>(
-                    FLCE_KIND_LOGITS_GEMM, Xc, H, W, H, Z, p.ldz, nullptr, 0, rows, V, H, s, 1, 0,
-                    n_live, 0)));
+                    FLCE_KIND_LOGITS_GEMM, Xc, H, W, H, Z, p.ldz, nullptr, 0, rows, V, H, s, 1, 0, dyn_m)));
         } else {
             FLCE_TRY((launch_gemm_generic<T, T>(FLCE_KIND_LOGITS_GEMM, Xc, H, W, H, Z, p.ldz, rows, V, H,
                                                 false, s)));
@@ -380,16 +411,16 @@ int run_head(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t
                         float* part = reinterpret_cast<float*>(ws + p.off_dxpart);
                         FLCE_TRY((launch_gemm_fast<float, void, false, true>(
                             FLCE_KIND_DX_GEMM, Z, p.ldz, W, H, part, H, nullptr, 0, rows, H, V, s,
-                            p.dx_ksplit, p.C * H, n_live, 0)));
+                            p.dx_ksplit, p.C * H, dyn_dx)));
                         FLCE_TRY(launch_splitk_reduce<bf16_t>(part, p.C * H, p.dx_ksplit, dXc, rows * H,
-                                                              add_in_gemm, s));
+                                                              add_in_gemm, s, dyn_dx.ksplit));
                     } else if (add_in_gemm) {
                         FLCE_TRY((launch_gemm_fast<bf16_t, bf16_t, false, true>(
                             FLCE_KIND_DX_GEMM, Z, p.ldz, W, H, dXc, H, dXc, H, rows, H, V, s)));
                     } else {
                         FLCE_TRY((launch_gemm_fast<bf16_t, void, false, true>(
                             FLCE_KIND_DX_GEMM, Z, p.ldz, W, H, dXc, H, nullptr, 0, rows, H, V, s, 1, 0,
-                            n_live, 0)));
+                            dyn_m)));
                     }
                 }
             } else {
@@ -439,19 +470,19 @@ int run_head(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t
                     if (p.nchunks == 1) {
                         FLCE_TRY((launch_gemm_fast<bf16_t, void, true, true>(
                             FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dW, H, nullptr, 0, V, H, rows, s, 1, 0,
-                            n_live, 1)));
+                            dyn_dw)));
                     } else if (c == 0) {
                         FLCE_TRY((launch_gemm_fast<float, void, true, true>(
                             FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dWacc, H, nullptr, 0, V, H, rows, s, 1, 0,
-                            n_live, 1)));
+                            dyn_dw)));
                     } else if (!last) {
                         FLCE_TRY((launch_gemm_fast<float, float, true, true>(
                             FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dWacc, H, dWacc, H, V, H, rows, s, 1, 0,
-                            n_live, 1)));
+                            dyn_dw)));
                     } else {   // last chunk: add the fp32 partial sums and write dW in bf16
                         FLCE_TRY((launch_gemm_fast<bf16_t, float, true, true>(
                             FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dW, H, dWacc, H, V, H, rows, s, 1, 0,
-                            n_live, 1)));
+                            dyn_dw)));
                     }
                 }
             } else {
@@ -617,7 +648,7 @@ int flce_multihead_fwd_bwd(const void* X, const void* const* W, const int64_t* c
     }
     if (ignore_index >= 0 && ignore_index < V) return FLCE_ERR_ARG;   // would shadow a class
 
-    const Plan p = make_plan(BT, H, V, dtype, effective_budget(V, dtype), false, g_compact);
+    const Plan p = plan_for(BT, H, V, dtype);
     char* ws = nullptr;
     FLCE_TRY(acquire_workspace(p.total, &ws));
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -646,7 +677,7 @@ int flce_rmsnorm_fwd_bwd(const void* h, const void* gamma, float eps, const void
     if (ignore_index >= 0 && ignore_index < V) return FLCE_ERR_ARG;
     if (!(eps >= 0.0f) || eps - eps != 0.0f) return FLCE_ERR_ARG;   // negative, NaN or infinite
 
-    const Plan p = make_plan(BT, H, V, dtype, effective_budget(V, dtype), false, g_compact);
+    const Plan p = plan_for(BT, H, V, dtype);
     const NormLayout l = norm_layout(p, H);
     char* ws = nullptr;
     FLCE_TRY(acquire_workspace(l.total, &ws));
@@ -666,7 +697,7 @@ int flce_rmsnorm_fwd_bwd(const void* h, const void* gamma, float eps, const void
 
 size_t flce_rmsnorm_workspace_bytes(int64_t BT, int64_t H, int64_t V, int dtype) {
     if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
-    return norm_layout(make_plan(BT, H, V, dtype, effective_budget(V, dtype), false, g_compact), H).total;
+    return norm_layout(plan_for(BT, H, V, dtype), H).total;
 }
 
 int flce_fwd_bwd_ex(const void* X, const void* W, const int64_t* targets, int64_t BT, int64_t H,
@@ -725,12 +756,12 @@ int flce_cross_entropy_inplace_noalloc(void* Z, const int64_t* targets, int64_t 
 
 size_t flce_workspace_bytes(int64_t BT, int64_t H, int64_t V, int dtype) {
     if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
-    return make_plan(BT, H, V, dtype, effective_budget(V, dtype), false, g_compact).total;
+    return plan_for(BT, H, V, dtype).total;
 }
 
 size_t flce_workspace_bytes_max(int64_t H, int64_t V, int dtype) {
     if (check_dims(1, H, V, dtype) != FLCE_OK) return 0;
-    return make_plan(0, H, V, dtype, effective_budget(V, dtype), true, g_compact).total;
+    return plan_for(0, H, V, dtype, true).total;
 }
 
 int flce_set_workspace(void* ws, size_t bytes) {
@@ -777,17 +808,17 @@ int flce_get_row_compaction(void) { return g_compact ? 1 : 0; }
 
 int64_t flce_chunk_rows(int64_t BT, int64_t H, int64_t V, int dtype) {
     if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
-    return make_plan(BT, H, V, dtype, effective_budget(V, dtype), false, g_compact).C;
+    return plan_for(BT, H, V, dtype).C;
 }
 
 int64_t flce_num_chunks(int64_t BT, int64_t H, int64_t V, int dtype) {
     if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
-    return make_plan(BT, H, V, dtype, effective_budget(V, dtype), false, g_compact).nchunks;
+    return plan_for(BT, H, V, dtype).nchunks;
 }
 
 int flce_dx_k_ranges(int64_t BT, int64_t H, int64_t V, int dtype) {
     if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
-    return make_plan(BT, H, V, dtype, effective_budget(V, dtype), false, g_compact).dx_ksplit;
+    return plan_for(BT, H, V, dtype).dx_ksplit;
 }
 
 int64_t flce_paper_chunk_rows(int64_t BT, int64_t H, int64_t V) {

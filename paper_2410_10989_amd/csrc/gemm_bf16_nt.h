@@ -93,6 +93,14 @@ struct FGArgs {
     // launched for the static size; workgroups of tiles past the dynamic M return at once.
     const int* dyn_rows;
     int dyn_is_k;
+    // Number of K ranges known on the device only: when not null, *dyn_ksplit (at most
+    // ksplit, which sizes the grid) replaces ksplit.
+    const int* dyn_ksplit;
+    // Chunk launches that may turn out empty: when first_live is not null, this launch
+    // (number `launch`) returns at once if launch < *first_live, and the addend Cin is
+    // taken as zero (not read) unless launch > *first_live.
+    const int* first_live;
+    int launch;
 };
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -278,17 +286,25 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
     const int wm = wave >> 1, wn = wave & 1;
 
     // ---- workgroup id -> (K range, tile) (XCD aware, grouped order) ----
-    int M = a.M, K = a.K;
+    int M = a.M, K = a.K, ksplit = a.ksplit;
+    bool use_in = HAS_IN;
+    if (a.first_live) {
+        const int fl = *a.first_live;   // uniform: a scalar load
+        if (a.launch < fl) return;
+        use_in = HAS_IN && a.launch > fl;
+    }
     if (a.dyn_rows) {
-        const int r = *a.dyn_rows;   // uniform: a scalar load
+        const int r = *a.dyn_rows;
         if (a.dyn_is_k) K = min(K, r); else M = min(M, r);
     }
+    if (a.dyn_ksplit) ksplit = min(ksplit, max(1, *a.dyn_ksplit));
+    (void)use_in;
     // The tile sequence covers the live rows only (a dynamic M can be smaller than the M the
     // grid was sized for): the live tiles are dealt evenly to the XCDs, and the workgroups
     // that are left over have the highest ids, are dispatched last and return at once.
     const int tiles_m = (M + FG_BM - 1) / FG_BM;
     const int tiles = tiles_m * a.tiles_n;
-    const int total = tiles * a.ksplit;
+    const int total = tiles * ksplit;
     const int per_xcd = (total + FG_XCDS - 1) / FG_XCDS;
     const int in_xcd = (int)blockIdx.x / FG_XCDS;
     const int seq_all = ((int)blockIdx.x % FG_XCDS) * per_xcd + in_xcd;
@@ -407,8 +423,8 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
 
     // K steps [k_begin, k_begin + nk) belong to this workgroup
     const int steps_all = (K + FG_BK - 1) / FG_BK;
-    const int k_begin = (int)((int64_t)steps_all * split / a.ksplit);
-    const int nk = (int)((int64_t)steps_all * (split + 1) / a.ksplit) - k_begin;
+    const int k_begin = (int)((int64_t)steps_all * split / ksplit);
+    const int nk = (int)((int64_t)steps_all * (split + 1) / ksplit) - k_begin;
     opa.start_at(k_begin);
     opb.start_at(k_begin);
     opa.load(smem, 0, 0, uwave);
@@ -432,6 +448,64 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
     if (t < nk) step(std::integral_constant<int, 1>{}, t++);
     if (t < nk) step(std::integral_constant<int, 2>{}, t++);
     if (t < nk) step(std::integral_constant<int, 3>{}, t++);
+    constexpr int ES = (int)sizeof(OutT);
+    constexpr int EW = 16 / ES;                 // output elements per lane and access: 4 or 8
+    constexpr int LANES_PER_ROW = 128 / EW;     // 32 or 16
+    constexpr int ROWS_PER_ACCESS = 64 / LANES_PER_ROW;   // rows one wavefront-wide access covers: 2 or 4
+    constexpr int PITCH = 128 + 4;              // fp32 words per staged row: 16 lanes' 16-byte writes of one column group hit 64 different banks
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int rows_c = min(FG_BM, M - m0);
+    const int ldc = (int)a.ldc, ldcin = (int)a.ldcin;
+    const __amdgpu_buffer_rsrc_t rsrc_c =
+        fg_make_rsrc(static_cast<OutT*>(a.C) + (int64_t)split * a.split_stride + (int64_t)m0 * a.ldc,
+                     (uint32_t)rows_c * (uint32_t)ldc * (uint32_t)ES);
+    __amdgpu_buffer_rsrc_t rsrc_in = rsrc_c;
+    if constexpr (HAS_IN)   // a range of zero bytes makes every addend load return zero without touching memory
+        rsrc_in = fg_make_rsrc(static_cast<const unsigned char*>(a.Cin) + (int64_t)m0 * a.ldcin * IS,
+                               use_in ? (uint32_t)rows_c * (uint32_t)ldcin * (uint32_t)IS : 0u);
+    const int uwm = __builtin_amdgcn_readfirstlane(wm), uwn = __builtin_amdgcn_readfirstlane(wn);
+    float* stage = reinterpret_cast<float*>(smem + uwave * (FG_LDS_BYTES / 4));   // 40 KB per wavefront
+    // output mapping of the lane: row (inside a group of ROWS_PER_ACCESS) and first column
+    const int orow = lane / LANES_PER_ROW, ocol = (lane % LANES_PER_ROW) * EW;
+    const int colw = n0 + uwn * 128;                       // first column of the wavefront's sub-tile
+    // columns are written in groups of EW; C rows must be allocated up to N rounded up to EW
+    const bool col_ok = colw + ocol < ((a.N + EW - 1) / EW) * EW;
+    const int lane_off = (orow * ldc + ocol) * ES;
+    const int lane_off_in = (orow * ldcin + ocol) * IS;
+    constexpr int NACC = 32 / ROWS_PER_ACCESS;             // accesses per 32-row pass: 16 or 8
+    constexpr int INW = HAS_IN ? EW * IS / 4 : 1;          // dwords of addend per lane and access
+    // Addend of pass `pass` (rows 32 pass .. + 31 of the wavefront's sub-tile) into buffer B.
+    // Two buffers: a pass's addend is requested one pass ahead, the first one before the last
+    // MFMAs of the K loop, so that the memory latency (a few thousand cycles: the addend comes
+    // from HBM) is not waited for in every pass.
+    uint32_t old2[HAS_IN ? 2 : 1][NACC][INW];
+    auto load_addend = [&](auto buf_, int pass) {
+        constexpr int B = decltype(buf_)::value;
+        const int row0 = uwm * 128 + pass * 32;
+#pragma unroll
+        for (int k = 0; k < NACC; ++k) {
+            const int soff = ((row0 + k * ROWS_PER_ACCESS) * ldcin + colw) * IS;
+            if constexpr (INW == 4) {
+                const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc_in, lane_off_in, soff, 0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) old2[B][k][e] = v[e];
+            } else if constexpr (INW == 8) {
+                const u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(rsrc_in, lane_off_in, soff, 0);
+                const u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(rsrc_in, lane_off_in + 16, soff, 0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    old2[B][k][e] = v0[e];
+                    old2[B][k][4 + e] = v1[e];
+                }
+            } else {   // 8 bf16 = 4 dwords, or 4 bf16 = 2 dwords
+                static_assert(INW == 2, "addend width");
+                const auto v = __builtin_amdgcn_raw_buffer_load_b64(rsrc_in, lane_off_in, soff, 0);
+                old2[B][k][0] = v[0];
+                old2[B][k][1] = v[1];
+            }
+        }
+    };
+    if constexpr (HAS_IN) load_addend(std::integral_constant<int, 0>{}, 0);
     {   // sub-step 3 of the last tile
         fg_wait(raw_a[1], raw_b[1]);
 #pragma unroll
@@ -459,60 +533,17 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
     // fewer memory instructions, each writing whole row segments.  Loads and stores go
     // through buffer descriptors that cover the tile's valid rows (rows past M are
     // dropped by the range check). ----
-    constexpr int ES = (int)sizeof(OutT);
-    constexpr int EW = 16 / ES;                 // output elements per lane and access: 4 or 8
-    constexpr int LANES_PER_ROW = 128 / EW;     // 32 or 16
-    constexpr int ROWS_PER_ACCESS = 64 / LANES_PER_ROW;   // rows one wavefront-wide access covers: 2 or 4
-    constexpr int PITCH = 128 + 4;              // fp32 words per staged row: 16 lanes' 16-byte writes of one column group hit 64 different banks
-    const int frow = lane & 31, fhalf = lane >> 5;
-    const int rows_c = min(FG_BM, M - m0);
-    const int ldc = (int)a.ldc, ldcin = (int)a.ldcin;
-    const __amdgpu_buffer_rsrc_t rsrc_c =
-        fg_make_rsrc(static_cast<OutT*>(a.C) + (int64_t)split * a.split_stride + (int64_t)m0 * a.ldc,
-                     (uint32_t)rows_c * (uint32_t)ldc * (uint32_t)ES);
-    __amdgpu_buffer_rsrc_t rsrc_in = rsrc_c;
-    if constexpr (HAS_IN)
-        rsrc_in = fg_make_rsrc(static_cast<const unsigned char*>(a.Cin) + (int64_t)m0 * a.ldcin * IS,
-                               (uint32_t)rows_c * (uint32_t)ldcin * (uint32_t)IS);
-    const int uwm = __builtin_amdgcn_readfirstlane(wm), uwn = __builtin_amdgcn_readfirstlane(wn);
-    float* stage = reinterpret_cast<float*>(smem + uwave * (FG_LDS_BYTES / 4));   // 40 KB per wavefront
-    // output mapping of the lane: row (inside a group of ROWS_PER_ACCESS) and first column
-    const int orow = lane / LANES_PER_ROW, ocol = (lane % LANES_PER_ROW) * EW;
-    const int colw = n0 + uwn * 128;                       // first column of the wavefront's sub-tile
-    // columns are written in groups of EW; C rows must be allocated up to N rounded up to EW
-    const bool col_ok = colw + ocol < ((a.N + EW - 1) / EW) * EW;
-    const int lane_off = (orow * ldc + ocol) * ES;
-    const int lane_off_in = (orow * ldcin + ocol) * IS;
-    constexpr int NACC = 32 / ROWS_PER_ACCESS;             // accesses per 32-row pass: 16 or 8
-    constexpr int INW = HAS_IN ? EW * IS / 4 : 1;          // dwords of addend per lane and access
 #pragma unroll
     for (int i = 0; i < 4; ++i) {                          // pass: rows 32 i .. 32 i + 31 of the sub-tile
         const int row0 = uwm * 128 + i * 32;
-        uint32_t old[NACC][INW];
-        if constexpr (HAS_IN) {                            // the pass's addend, before anything waits on it
-#pragma unroll
-            for (int k = 0; k < NACC; ++k) {
-                const int soff = ((row0 + k * ROWS_PER_ACCESS) * ldcin + colw) * IS;
-                if constexpr (INW == 4) {
-                    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc_in, lane_off_in, soff, 0);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) old[k][e] = v[e];
-                } else if constexpr (INW == 8) {
-                    const u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(rsrc_in, lane_off_in, soff, 0);
-                    const u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(rsrc_in, lane_off_in + 16, soff, 0);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        old[k][e] = v0[e];
-                        old[k][4 + e] = v1[e];
-                    }
-                } else {   // 8 bf16 = 4 dwords, or 4 bf16 = 2 dwords
-                    static_assert(INW == 2, "addend width");
-                    const auto v = __builtin_amdgcn_raw_buffer_load_b64(rsrc_in, lane_off_in, soff, 0);
-                    old[k][0] = v[0];
-                    old[k][1] = v[1];
-                }
-            }
+        // the next pass's addend is requested before this pass is staged: it arrives while this
+        // pass goes through LDS
+        if constexpr (HAS_IN) {
+            if (i == 0) load_addend(std::integral_constant<int, 1>{}, 1);
+            if (i == 1) load_addend(std::integral_constant<int, 0>{}, 2);
+            if (i == 2) load_addend(std::integral_constant<int, 1>{}, 3);
         }
+        uint32_t (&old)[NACC][INW] = old2[HAS_IN ? (i & 1) : 0];
         // stage the pass: the lane holds row frow and, per group of four registers, the four
         // consecutive columns 32 j + 8 (g/4) + 4 fhalf .. + 3 (the MFMAs are fed B first, A
         // second, so the accumulators hold the transposed 32 x 32 tiles): one 16-byte LDS

@@ -30,9 +30,11 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ in
 // With ADD the previous content of out is added as well (dX summed over heads).
 // VEC4: four elements per thread and access (n, split_stride and the pointers' element
 // offsets are multiples of 4); the additions per element are the same either way.
+// dyn_nsplit (optional): the number of ranges when only the device knows it.
 template <typename T, bool ADD, bool VEC4>
 __global__ void splitk_reduce_kernel(const float* __restrict__ part, int64_t split_stride, int nsplit,
-                                     T* __restrict__ out, int64_t n) {
+                                     T* __restrict__ out, int64_t n, const int* __restrict__ dyn_nsplit) {
+    if (dyn_nsplit) nsplit = *dyn_nsplit;
     if constexpr (VEC4) {
         typedef float f32x4v __attribute__((ext_vector_type(4)));
         for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4; i < n;

@@ -12,6 +12,12 @@
 
 #include <algorithm>
 
+#if defined(__HIPCC__)
+#define FLCE_HD __host__ __device__
+#else
+#define FLCE_HD
+#endif
+
 namespace flce {
 
 constexpr int64_t CHUNK_ALIGN = 256;   // chunk rows are a multiple of the GEMM macro tile
@@ -42,28 +48,34 @@ struct Plan {
 // into, so that tiles * ranges fills whole rounds of the chip's 256 CUs (one tile per
 // CU at a time).  288 tiles, for example, run as two rounds at 56 % occupancy; cut
 // into 8 ranges they are 9 full rounds.  Prefers few ranges (each costs an fp32
-// partial result) and keeps ranges long; with many rounds the tail does not matter
-// and the answer is 1.
-inline int choose_ksplit(int64_t tiles, int64_t ksteps, int max_ranges) {
+// partial result: a larger count must fill the rounds better by more than 2 % of the
+// chip, and more than 8 are only taken while they fill a first round) and keeps ranges
+// at least 64 K steps long; with many rounds the tail does not
+// matter and the answer is 1.  Integer arithmetic only: the host and the device (which
+// knows the live row count of a compacted chunk) must agree on the answer.
+FLCE_HD inline int choose_ksplit(int64_t tiles, int64_t ksteps, int max_ranges) {
     constexpr int64_t CUS = 256, MIN_STEPS = 64;
     int best = 1;
-    double best_eff = 0.0;
+    int64_t best_work = 0, best_rounded = 1;   // occupancy of the best choice = best_work / best_rounded
     for (int s = 1; s <= 16 && s <= max_ranges && ksteps / s >= MIN_STEPS; ++s) {
         const int64_t work = tiles * s;
-        const double eff = (double)work / (double)(((work + CUS - 1) / CUS) * CUS);
-        if (eff > best_eff + 0.02) {
-            best_eff = eff;
+        if (s > 8 && work > CUS) break;   // more than 8 ranges only to fill a first round
+        const int64_t rounded = ((work + CUS - 1) / CUS) * CUS;
+        // work / rounded > best_work / best_rounded + 1/50
+        if (rounded > 0 && 50 * work * best_rounded > (50 * best_work + best_rounded) * rounded) {
+            best_work = work;
+            best_rounded = rounded;
             best = s;
         }
     }
     return best;
 }
 
-// The fp32 partial results of a cut dX product (ranges x rows x H) may take as much
+// The fp32 partial results of a cut dX product (ranges x rows x H) may take half as much
 // memory as the logits chunk, not more.
 inline int max_dx_ranges(size_t budget_bytes, int64_t rows, int64_t H) {
     const size_t one = (size_t)rows * (size_t)H * sizeof(float);
-    const size_t n = one ? budget_bytes / one : 1;
+    const size_t n = one ? budget_bytes / 2 / one : 1;
     return (int)std::max<size_t>(1, std::min<size_t>(n, 16));
 }
 
@@ -82,32 +94,14 @@ inline int dx_ranges(bool tuned, int64_t rows, int64_t H, int64_t V, size_t budg
 inline bool fits_row_form(int64_t ld, int64_t) { return 256 * ld * 2 + 128 < ((int64_t)1 << 30); }
 inline bool fits_col_form(int64_t ld, int64_t) { return 64 * ld * 2 + 512 < ((int64_t)1 << 30); }
 
-inline Plan make_plan(int64_t BT, int64_t H, int64_t V, int dtype, size_t budget_bytes,
-                      bool worst_case_bt = false, bool allow_compact = true) {
-    Plan p;
+// Byte offsets of the workspace for a plan whose chunking (C, nchunks, rows of the last
+// chunk) is decided; `dxpart_floor` is a lower bound for the K-range partials.
+inline void lay_out(Plan& p, int64_t H, int64_t V, int dtype, int64_t rows_last, size_t budget_bytes,
+                    bool allow_compact, size_t dxpart_floor) {
     const size_t es = elem_size(dtype);
-    p.ldz = round_up(V, 64);
-    int64_t cmax = (int64_t)(budget_bytes / ((size_t)p.ldz * es));
-    cmax = cmax / CHUNK_ALIGN * CHUNK_ALIGN;
-    if (cmax < CHUNK_ALIGN) cmax = CHUNK_ALIGN;
-    int64_t rows_last;
-    if (worst_case_bt) {
-        p.C = cmax;
-        p.nchunks = 2;
-        rows_last = 1;   // a ragged last chunk is the most expensive case
-    } else if (BT <= cmax) {
-        p.C = BT;
-        p.nchunks = 1;
-        rows_last = BT;
-    } else {
-        p.nchunks = (BT + cmax - 1) / cmax;
-        p.C = round_up((BT + p.nchunks - 1) / p.nchunks, CHUNK_ALIGN);   // even out the chunks
-        p.nchunks = (BT + p.C - 1) / p.C;
-        rows_last = BT - (p.nchunks - 1) * p.C;
-    }
     p.ldc = round_up(p.C, 64);
     p.fp32_dw_acc = (dtype != 0) && p.nchunks > 1;
-
+    p.fast_logits = p.fast_dx = p.fast_dw_full = p.fast_dw_last = false;
     if (dtype != 0) {
         const bool out_ok = 256 * H * 4 < ((int64_t)1 << 31);
         p.fast_logits = (H % 64 == 0) && fits_row_form(H, H) && 256 * p.ldz * 2 < ((int64_t)1 << 31);
@@ -142,16 +136,8 @@ inline Plan make_plan(int64_t BT, int64_t H, int64_t V, int dtype, size_t budget
     p.off_wt = take(need_wt ? (size_t)H * p.ldz * es : 0);
     p.off_xt = take(need_gt ? (size_t)H * p.ldc * es : 0);
     p.off_dwacc = take(p.fp32_dw_acc ? (size_t)V * H * sizeof(float) : 0);
-    size_t dxpart = p.dx_ksplit > 1 ? (size_t)p.dx_ksplit * p.C * H * sizeof(float) : 0;
-    if (worst_case_bt) {
-        // the bound has to hold for every chunk size the scheduler can pick (the number of
-        // ranges depends on the row count through its count of 128-row tiles only)
-        for (int64_t c = 128; c <= cmax; c += 128) {
-            const int ks = dx_ranges(p.fast_dx, c, H, V, budget_bytes);
-            if (ks > 1) dxpart = std::max(dxpart, (size_t)ks * c * H * sizeof(float));
-        }
-    }
-    p.off_dxpart = take(dxpart);
+    const size_t dxpart = p.dx_ksplit > 1 ? (size_t)p.dx_ksplit * p.C * H * sizeof(float) : 0;
+    p.off_dxpart = take(std::max(dxpart, dxpart_floor));
     // a chunk of gathered input rows and of their gradient (also the normalised rows and
     // their gradient when an RMSNorm runs in front), index maps of the compaction
     p.off_xg = take((size_t)p.C * H * es);
@@ -160,6 +146,62 @@ inline Plan make_plan(int64_t BT, int64_t H, int64_t V, int dtype, size_t budget
     p.off_tv = take(p.compact ? (size_t)p.C * sizeof(int64_t) : 0);
     p.off_dyn = take(256);
     p.total = off;
+}
+
+// budget_bytes bounds one chunk of logits.  A batch whose WHOLE logits fit in
+// single_bytes (>= budget_bytes) runs as one chunk whatever the budget says: the
+// automatic rule passes the chunk budget plus the size of the fp32 dW partial sums,
+// which only several chunks need, so that one chunk is taken whenever it needs no more
+// memory than the chunked plan would (and it is always faster: no second pass over W,
+// no fp32 round trip of dW).  worst_case_bt: the plan with the largest workspace any BT
+// can lead to (BT is ignored).
+inline Plan make_plan(int64_t BT, int64_t H, int64_t V, int dtype, size_t budget_bytes,
+                      bool worst_case_bt = false, bool allow_compact = true, size_t single_bytes = 0) {
+    Plan p;
+    const size_t es = elem_size(dtype);
+    p.ldz = round_up(V, 64);
+    const size_t row_bytes = (size_t)p.ldz * es;
+    int64_t cmax = (int64_t)(budget_bytes / row_bytes);
+    cmax = cmax / CHUNK_ALIGN * CHUNK_ALIGN;
+    if (cmax < CHUNK_ALIGN) cmax = CHUNK_ALIGN;
+    const int64_t single_max = std::max<int64_t>(cmax, (int64_t)(single_bytes / row_bytes));   // rows
+    if (worst_case_bt) {
+        // the bound has to hold for every chunk size the scheduler can pick: the number of
+        // K ranges of the dX product depends on the row count through its tile count
+        auto dxpart_over = [&](bool tuned, int64_t upto) {
+            size_t m = 0;
+            for (int64_t c = 128; c <= upto; c += 128) {
+                const int ks = dx_ranges(tuned, c, H, V, budget_bytes);
+                if (ks > 1) m = std::max(m, (size_t)ks * c * H * sizeof(float));
+            }
+            return m;
+        };
+        // several chunks, the last one ragged (the most expensive case) ...
+        p.C = cmax;
+        p.nchunks = 2;
+        lay_out(p, H, V, dtype, 1, budget_bytes, allow_compact, 0);
+        lay_out(p, H, V, dtype, 1, budget_bytes, allow_compact, dxpart_over(p.fast_dx, cmax));
+        // ... or the largest batch that still runs as one chunk
+        Plan q;
+        q.ldz = p.ldz;
+        q.C = single_max;
+        q.nchunks = 1;
+        lay_out(q, H, V, dtype, single_max, budget_bytes, allow_compact, 0);
+        lay_out(q, H, V, dtype, single_max, budget_bytes, allow_compact, dxpart_over(q.fast_dx, single_max));
+        return q.total > p.total ? q : p;
+    }
+    int64_t rows_last;
+    if (BT <= single_max) {
+        p.C = BT;
+        p.nchunks = 1;
+        rows_last = BT;
+    } else {
+        p.nchunks = (BT + cmax - 1) / cmax;
+        p.C = round_up((BT + p.nchunks - 1) / p.nchunks, CHUNK_ALIGN);   // even out the chunks
+        p.nchunks = (BT + p.C - 1) / p.C;
+        rows_last = BT - (p.nchunks - 1) * p.C;
+    }
+    lay_out(p, H, V, dtype, rows_last, budget_bytes, allow_compact, 0);
     return p;
 }
 

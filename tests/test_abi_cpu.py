@@ -54,7 +54,17 @@ def test_workspace_is_bounded_independently_of_BT(H, V):
     C = flce.flce_chunk_rows(10 ** 7, H, V, code)
     sizes = [flce.flce_workspace_bytes(bt, H, V, code) for bt in (C, 2 * C, 4 * C, 8 * C, 64 * C)]
     assert all(0 < s <= cap for s in sizes)
-    assert len(set(sizes[1:])) == 1          # constant once BT exceeds one chunk
+    # A batch whose whole logits take no more memory than one chunk plus the fp32 dW partial
+    # sums of a chunked run is not chunked at all (smaller and faster); beyond that the
+    # workspace is constant
+    single_rows = (max(1 << 30, 4096 * V * 2) + V * H * 4) // (V * 2)
+    for bt in (single_rows - 300, single_rows):
+        assert flce.flce_num_chunks(bt, H, V, code) == 1
+        assert flce.flce_workspace_bytes(bt, H, V, code) <= cap
+    assert flce.flce_num_chunks(single_rows + 1, H, V, code) > 1
+    many = [flce.flce_workspace_bytes(bt, H, V, code) for bt in (single_rows + 1, 4 * C, 8 * C, 64 * C, 4096 * C)
+            if bt % C == 0 or bt == single_rows + 1]
+    assert len(set(many[1:])) == 1 and all(s <= cap for s in many)
     # a chunk whose row count is not a multiple of 64 takes the guarded kernels, which
     # need transposed scratch: larger, but still bounded by the same cap for any BT
     ragged = [flce.flce_workspace_bytes(bt, H, V, code) for bt in (C + 1, 9 * C + 3, 10 ** 7 + 1)]
@@ -64,7 +74,7 @@ def test_workspace_is_bounded_independently_of_BT(H, V):
     assert C % 256 == 0 and C * V * 2 <= budget and C >= 4096
     for bt in (1, 255, C, C + 1, 3 * C - 5):
         c, n = flce.flce_chunk_rows(bt, H, V, code), flce.flce_num_chunks(bt, H, V, code)
-        assert c * n >= bt > c * (n - 1) and c <= max(C, 256)
+        assert c * n >= bt > c * (n - 1) and (c <= max(C, 256) or (n == 1 and c <= single_rows))
         assert flce.flce_workspace_bytes(bt, H, V, code) <= cap
 
 

@@ -323,9 +323,9 @@ def _with_budget_rows(rows_per_chunk, V, fn):
 
 
 @pytest.mark.parametrize("frac", [0.9, 0.5, 0.26])
-def test_mostly_ignored_rows_leave_trailing_chunks_empty(frac):
-    # 4 chunks of 256 rows are launched; the valid rows fill only the first one(s), the others run
-    # with zero live rows (their dW launches only pass the partial sums on)
+def test_mostly_ignored_rows_leave_leading_chunks_empty(frac):
+    # 4 chunks of 256 rows are launched; the valid rows are dealt evenly to the last one(s), the
+    # launches before them run with zero live rows (their dW launches return at once)
     import paper_2410_10989_amd as flce
     w = workloads.make(1024, 128, 1000, "bf16", ignore=("iid", frac), seed=900 + int(frac * 100),
                        name="sparse_targets")
