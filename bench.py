@@ -4,15 +4,29 @@
 
 One step = one pass of the whole hot path (count, chunked logits GEMM, in-place
 cross entropy, dX GEMM, dW GEMM, finalize) over one synthetic batch that is
-already resident in HBM.  Prints ONE JSON line: tokens/s for forward+backward,
-the roofline of the dominant kernel (per-launch algorithmic flops over its
-average launch time, HIP events on the launch stream), and the CPU oracle timed
-on a bounded sample of the same workload.
+already resident in HBM.  Prints ONE JSON line:
+
+  value / ms_per_step    K passes in the library's default configuration, timed
+                         with per-kernel timing OFF (wall clock around a synchronised
+                         loop); socket power sampled meanwhile
+  product_rooflines      a second, short loop with the library's per-kernel HIP events
+                         on: per product class (logits, dX, dW) the executed flops per
+                         launch over the mean launch time; `roofline` is the class that
+                         takes the most time per step
+  dense                  the same workload with row compaction off (every row projected,
+                         as the paper does)
+  per_config             all five benchmark workloads, a few passes each
+  memory                 workspace against the full logits for growing BT
+  mfma_only_loop         the MFMA instruction alone on register operands, with power
+  cpu_baseline           the CPU oracle on a bounded sample of the same workload
 """
 import argparse
+import glob
 import json
 import os
+import re
 import sys
+import threading
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -21,13 +35,66 @@ if ROOT not in sys.path:
 
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense matrix peaks
 HBM_PEAK_GBS = 8000.0
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "gemm_bf16_256_config3_hbm_traffic.txt")
 
-# HBM bytes per launch of the dominant kernel (logits product at config 3) from
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, each scaled by what
-# the same counter reads for the 1 GiB copy of --calibrate-copy; the summary of
-# those runs is profiles/gemm_bf16_256_config3_hbm_traffic.txt.  Only valid for
-# the default workload.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 9.35e9
+
+def measured_traffic_bytes():
+    """HBM-side bytes per launch of each product class at the default workload, from the
+    committed rocprofv3 counter summary (FETCH_SIZE and WRITE_SIZE runs, each scaled by
+    what the same counter reads for a plain copy of known size): the line
+    '# bench.py: traffic_bytes_per_launch logits=... dx=... dw=...' of that file."""
+    try:
+        text = open(TRAFFIC_PROFILE).read()
+    except OSError:
+        return {}
+    m = re.search(r"traffic_bytes_per_launch\s+(.*)", text)
+    if not m:
+        return {}
+    return {k: float(v) for k, v in re.findall(r"(\w+)=([0-9.eE+]+)", m.group(1))}
+
+
+class PowerSampler:
+    """Socket power of the GPU from the amdgpu hwmon node (microwatts), sampled by a
+    thread every 20 ms while a region runs."""
+
+    def __init__(self):
+        nodes = sorted(glob.glob("/sys/class/drm/card[0-9]*/device/hwmon/hwmon*/power1_input"))
+        self.path = nodes[0] if nodes else None
+        self.cap_w = None
+        if self.path:
+            try:
+                self.cap_w = int(open(os.path.join(os.path.dirname(self.path), "power1_cap")).read()) / 1e6
+            except (OSError, ValueError):
+                pass
+        self.samples = []
+        self._stop = False
+        self._thread = None
+
+    def _run(self):
+        while not self._stop:
+            try:
+                self.samples.append(int(open(self.path).read()) / 1e6)
+            except (OSError, ValueError):
+                pass
+            time.sleep(0.02)
+
+    def __enter__(self):
+        if self.path:
+            self._thread = threading.Thread(target=self._run, daemon=True)
+            self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop = True
+        if self._thread:
+            self._thread.join()
+
+    def summary(self, skip_s=0.3):
+        """Mean / max over the region without its first `skip_s` seconds (ramp-up)."""
+        s = self.samples[int(skip_s / 0.02):] or self.samples
+        if not s:
+            return None
+        return {"mean_w": sum(s) / len(s), "max_w": max(s), "cap_w": self.cap_w, "samples": len(s)}
 
 
 def bench_cross_entropy(args):
@@ -81,6 +148,59 @@ def bench_cross_entropy(args):
         "sweep": rows}), flush=True)
 
 
+def upload(w):
+    import numpy as np
+    import torch
+
+    import workloads
+    if w.dtype == "bf16":
+        up = lambda a: torch.from_numpy(workloads.bf16_bits(a).view(np.int16)).cuda().view(torch.bfloat16)
+    else:
+        up = lambda a: torch.from_numpy(a).cuda()
+    return up(w.X), up(w.W), torch.from_numpy(w.targets).cuda(), up
+
+
+def time_steps(step, warmup, steps, with_power=False):
+    """`steps` calls of step() after `warmup` untimed ones, bracketed by device
+    synchronisation; returns (ms per step, sorted per-step ms from events on the call's
+    stream, power summary or None)."""
+    import torch
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    sampler = PowerSampler() if with_power else None
+    if sampler:
+        sampler.__enter__()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    marks[0].record()
+    for k in range(steps):
+        step()
+        marks[k + 1].record()
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    if sampler:
+        sampler.__exit__()
+    per_step = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(steps))
+    # a region shorter than the ramp-up skip would leave nothing: skip less then
+    power = sampler.summary(skip_s=min(0.3, (t2 - t1) / 4)) if sampler else None
+    return (t2 - t1) * 1e3 / steps, per_step, power
+
+
+def config_line(flce, w, code, ms, compaction, nh=1, flop_factor=6.0):
+    """Throughput figures of one timed configuration."""
+    rows = w.n_valid if compaction else w.BT
+    nominal = flop_factor * w.BT * w.H * w.V * nh / (ms * 1e-3) / 1e12
+    return {"ms_per_step": ms, "tokens_per_s": w.BT / (ms * 1e-3),
+            "tflops_executed": nominal * rows / w.BT, "tflops_over_6BTHV": nominal,
+            "rows_projected": rows, "row_compaction": bool(compaction),
+            "chunks": flce.flce_num_chunks(w.BT, w.H, w.V, code),
+            "chunk_rows": flce.flce_chunk_rows(w.BT, w.H, w.V, code),
+            "peak_extra_hbm_mb": flce.flce_workspace_bytes(w.BT, w.H, w.V, code) / 1e6,
+            "full_logits_avoided_mb": flce.flce_full_logits_bytes(w.BT, w.V, code) / 1e6}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -99,11 +219,13 @@ def main():
     ap.add_argument("--skip-dx", action="store_true",
                     help="frozen backbone (Medusa stage 1): no hidden-state gradient")
     ap.add_argument("--no-compaction", action="store_true",
-                    help="project every row, also those with an ignored target (A/B of the row compaction)")
+                    help="project every row, also those with an ignored target, in the headline leg too")
     ap.add_argument("--rmsnorm", action="store_true",
                     help="time flce_rmsnorm_fwd_bwd: RMSNorm of raw hidden states fused in front (one head)")
     ap.add_argument("--no-mfma-loop", action="store_true",
                     help="skip the MFMA-only loop that is reported beside the roofline")
+    ap.add_argument("--no-dense-leg", action="store_true", help="skip the leg with row compaction off")
+    ap.add_argument("--no-per-config", action="store_true", help="skip the passes over the other four workloads")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one plain 1 GiB device copy first (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -112,7 +234,6 @@ def main():
               "pipeline; no collectives are part of it). Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
 
     import paper_2410_10989_amd as flce
@@ -131,13 +252,7 @@ def main():
     w = workloads.make_config(args.config)
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     code = flce.FLCE_BF16 if w.dtype == "bf16" else flce.FLCE_F32
-
-    def up(a):
-        if w.dtype == "bf16":
-            return torch.from_numpy(workloads.bf16_bits(a).view(np.int16)).cuda().view(torch.bfloat16)
-        return torch.from_numpy(a).cuda()
-
-    X, W, t = up(w.X), up(w.W), torch.from_numpy(w.targets).cuda()
+    X, W, t, up = upload(w)
     dX, dW = torch.empty_like(X), torch.empty_like(W)
     loss = torch.empty((), dtype=torch.float32, device="cuda")
     print(f"# inputs {w.name} BT={w.BT} H={w.H} V={w.V} {w.dtype} generated+uploaded in "
@@ -152,6 +267,7 @@ def main():
 
     nh = args.heads
     flags = flce.SKIP_DX if args.skip_dx else 0
+    variant = nh > 1 or args.rmsnorm or args.skip_dx
     if nh > 1:
         # extra heads: seeded N(0, 0.02^2) weights drawn on the device; head j's target at
         # position p is head 0's target at p + j inside sequences of 2048 tokens
@@ -192,45 +308,48 @@ def main():
     rows_projected = sum(int((x != w.ignore_index).sum().item()) for x in all_targets) if compaction \
         else w.BT * nh
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-
-    flce.flce_timing_enable(True)
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    marks[0].record()
-    for k in range(args.steps):
-        step()
-        marks[k + 1].record()      # same stream as the call: per-step times for the quantiles
-    torch.cuda.synchronize()
-    t2 = time.perf_counter()
-    per_step = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps))
+    # ---- headline leg: per-kernel timing off ----
+    ms_per_step, per_step, power = time_steps(step, args.warmup, args.steps, with_power=True)
     quantile = lambda q: per_step[int(round(q * (len(per_step) - 1)))]
-    flce.flce_timing_enable(False)
-    kt = flce.flce_timing_collect()
-    ms_per_step = (t2 - t1) * 1e3 / args.steps
+    loss_value = float(loss.item())
     tokens_per_s = w.BT / (ms_per_step * 1e-3)
-
-    flops_step = (4.0 if args.skip_dx else 6.0) * w.BT * w.H * w.V * nh
-    tflops = flops_step / (ms_per_step * 1e-3) / 1e12
+    flop_factor = 4.0 if args.skip_dx else 6.0
+    flops_step = flop_factor * w.BT * w.H * w.V * nh
+    tflops_nominal = flops_step / (ms_per_step * 1e-3) / 1e12
+    tflops_executed = tflops_nominal * rows_projected / (w.BT * nh)
     peak = MFMA_PEAK_TFLOPS[w.dtype]
 
-    # Dominant kernel = the kernel symbol with the largest total time.  The logits and
-    # dX products are one symbol each; with several chunks the dW product runs as
-    # two symbols (fp32 partial sums, then the bf16 result), so its time is split.
+    # ---- breakdown leg: the same passes with HIP events around every kernel launch ----
+    bsteps = max(1, min(args.steps, 5))
+    flce.flce_timing_enable(True)
+    for _ in range(bsteps):
+        step()
+    torch.cuda.synchronize()
+    flce.flce_timing_enable(False)
+    kt = flce.flce_timing_collect()
     nchunks = flce.flce_num_chunks(w.BT, w.H, w.V, code)
     gemm_kinds = ("logits_gemm", "dw_gemm") if args.skip_dx else ("logits_gemm", "dx_gemm", "dw_gemm")
-    symbols = {"logits_gemm": 1, "dx_gemm": 1, "dw_gemm": 2 if nchunks > 1 else 1}
-    dom = max(gemm_kinds, key=lambda k: kt[k][0] / symbols[k])
-    dom_ms, dom_n = kt[dom]
-    # executed flops of the dominant kernel, mean over its launches (ignored rows are not projected)
-    flops_per_launch = 2.0 * rows_projected * w.H * w.V * args.steps / max(dom_n, 1)
-    dom_avg_ms = dom_ms / max(dom_n, 1)
-    achieved = flops_per_launch / (dom_avg_ms * 1e-3) / 1e12 if dom_n else 0.0
+    traffic = measured_traffic_bytes() if (args.config == 3 and not variant and not args.budget_mib
+                                           and compaction) else {}
+    # One product launch per chunk, head and class (the K-range reduction of a cut dX product is
+    # booked with it).  Executed flops of a class per step: 2 * rows projected * H * V.
+    launches_per_step = nchunks * nh
+    class_flops_step = 2.0 * rows_projected * w.H * w.V
+    rooflines = {}
+    for k in gemm_kinds:
+        ms_step = kt[k][0] / bsteps
+        avg_launch_ms = ms_step / launches_per_step
+        ach = class_flops_step / launches_per_step / (avg_launch_ms * 1e-3) / 1e12 if ms_step > 0 else 0.0
+        short = {"logits_gemm": "logits", "dx_gemm": "dx", "dw_gemm": "dw"}[k]
+        rooflines[short] = {"bound": "mfma", "kernel": k, "achieved": ach, "peak": peak, "unit": "TFLOP/s",
+                            "frac": ach / peak, "ms_per_step": ms_step, "avg_launch_ms": avg_launch_ms,
+                            "launches_per_step": launches_per_step,
+                            "flops_per_launch": class_flops_step / launches_per_step,
+                            "traffic": traffic.get(short)}
+    dom = max(rooflines, key=lambda s: rooflines[s]["ms_per_step"])
     ce_ms, ce_n = kt["ce_rows"]
-    ce_gbs = (2.0 * w.BT * w.V * (2 if w.dtype == "bf16" else 4) * args.steps) / (ce_ms * 1e-3) / 1e9 if ce_n else 0.0
+    elem = 2 if w.dtype == "bf16" else 4
+    ce_gbs = (2.0 * rows_projected * w.V * elem * bsteps) / (ce_ms * 1e-3) / 1e9 if ce_n else 0.0
 
     out = {
         "metric": ("RMSNorm + " if args.rmsnorm else "") +
@@ -253,28 +372,44 @@ def main():
                    flce.flce_chunk_rows(w.BT, w.H, w.V, code), "chunks": nchunks,
                    "logits_budget_mib": (flce.flce_get_logits_budget_bytes() >> 20) or "auto"},
         "heads": nh,
-        "tflops_over_6BTHV": tflops,   # nominal: over 6*BT*H*V per head (4*BT*H*V without dX)
-        "mfma_util_frac_of_peak": tflops / peak,
-        # rows with an ignored target are left out of the products (row compaction): what the
-        # matrix cores really executed is smaller than the nominal count by this share
+        # rows with an ignored target are left out of the products (row compaction): the matrix
+        # cores execute 6 * rows_projected * H * V flops, not the nominal 6 * BT * H * V
         "row_compaction": bool(compaction),
         "rows_projected": rows_projected,
-        "tflops_executed": tflops * rows_projected / (w.BT * nh),
+        "tflops_executed": tflops_executed,
+        "mfma_util_frac_of_peak": tflops_executed / peak,
+        "tflops_over_6BTHV": tflops_nominal,
+        "mfma_util_frac_of_peak_nominal": tflops_nominal / peak,
         "peak_extra_hbm_mb": (flce.flce_rmsnorm_workspace_bytes if args.rmsnorm else
                               flce.flce_workspace_bytes)(w.BT, w.H, w.V, code) / 1e6,
         "full_logits_avoided_mb": flce.flce_full_logits_bytes(w.BT, w.V, code) / 1e6,
-        "loss": float(loss.item()),
-        "kernel_ms_per_step": {k: kt[k][0] / args.steps for k in kt},
+        "loss": loss_value,
+        "socket_power": power,
+        "kernel_ms_per_step": {k: kt[k][0] / bsteps for k in kt},
+        "kernel_timing_steps": bsteps,
         "ce_rows_hbm_gbs": ce_gbs,
-        "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": peak,
-                     "unit": "TFLOP/s", "frac": achieved / peak,
-                     "avg_launch_ms": dom_avg_ms, "launches": dom_n,
-                     "flops_per_launch": flops_per_launch,
-                     # the same with the nominal count (every row of the batch, ignored or not)
-                     "achieved_nominal": achieved * (w.BT * nh) / rows_projected,
-                     "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH
-                     if args.config == 3 and dom == "logits_gemm" and not args.budget_mib else None},
+        "roofline": dict(rooflines[dom], dominant_of=sorted(rooflines)),
+        "product_rooflines": rooflines,
     }
+
+    # memory: the workspace is bounded whatever BT is; the logits it stands in for grow with BT
+    out["memory"] = [{"BT": bt, "peak_extra_hbm_mb": flce.flce_workspace_bytes(bt, w.H, w.V, code) / 1e6,
+                      "full_logits_avoided_mb": flce.flce_full_logits_bytes(bt, w.V, code) / 1e6,
+                      "chunks": flce.flce_num_chunks(bt, w.H, w.V, code)}
+                     for bt in (w.BT, 4 * w.BT, 16 * w.BT)]
+    out["memory_bound_any_BT_mb"] = flce.flce_workspace_bytes_max(w.H, w.V, code) / 1e6
+
+    # ---- dense leg: every row projected, as the paper does ----
+    if compaction and not args.no_dense_leg:
+        flce.flce_set_row_compaction(False)
+        try:
+            dms, _, _ = time_steps(step, 2, bsteps)
+        finally:
+            flce.flce_set_row_compaction(True)
+        dn = flops_step / (dms * 1e-3) / 1e12
+        out["dense"] = {"what": "row compaction off: all BT rows projected", "ms_per_step": dms,
+                        "tokens_per_s": w.BT / (dms * 1e-3), "tflops_executed": dn,
+                        "mfma_util_frac_of_peak": dn / peak, "steps": bsteps}
 
     if w.dtype == "bf16" and not args.no_mfma_loop:
         # What the matrix pipes sustain with nothing to feed them from memory: the same MFMA
@@ -283,26 +418,62 @@ def main():
         # 4 x 4 fragments per K sub-step) the chip clocks far lower than on zeros.
         scratch = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
 
-        def mfma_loop(pattern):
-            # a train of launches back to back, as long as a few passes of the path: the clock
-            # settles within the first launches, which are left out
+        def mfma_loop(pattern, launches=160):
+            # a train of launches back to back (about 0.4 s): the clock settles within the
+            # first launches, which are left out
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             fl = 0.0
-            for k in range(16):
-                if k == 4:
-                    e0.record()
-                one = flce.flce_mfma_ceiling_launch(pattern, 256, 8000, 0.02, scratch)
-                fl += one if k >= 4 else 0.0
-            e1.record()
-            e1.synchronize()
-            return fl / (e0.elapsed_time(e1) * 1e-3) / 1e12
+            with PowerSampler() as ps:
+                for k in range(launches):
+                    if k == 8:
+                        e0.record()
+                    one = flce.flce_mfma_ceiling_launch(pattern, 256, 8000, 0.02, scratch)
+                    fl += one if k >= 8 else 0.0
+                e1.record()
+                e1.synchronize()
+            return fl / (e0.elapsed_time(e1) * 1e-3) / 1e12, ps.summary(skip_s=0.1)
 
-        rnd, zero = mfma_loop(2), mfma_loop(0)
+        (rnd, rnd_p), (zero, zero_p) = mfma_loop(2), mfma_loop(0)
         out["mfma_only_loop"] = {
             "random_operands_tflops": rnd, "zero_operands_tflops": zero,
+            "random_operands_power": rnd_p, "zero_operands_power": zero_p,
             "what": "v_mfma_f32_32x32x16_bf16 on register operands, no memory traffic, 256 workgroups x 4 "
-                    "wavefronts, 12 launches of ~3 ms back to back after 4 to settle the clock; random = N(0,1) x N(0,0.02^2) fragments, 4 A x 4 B per 16 MFMAs"}
-        out["roofline"]["frac_of_mfma_only_loop_random"] = achieved / rnd if rnd > 0 else None
+                    "wavefronts, 152 launches of ~2-3 ms back to back after 8 to settle the clock; "
+                    "random = N(0,1) x N(0,0.02^2) fragments, 4 A x 4 B per 16 MFMAs"}
+        for r in out["product_rooflines"].values():
+            r["frac_of_mfma_only_loop_random"] = r["achieved"] / rnd if rnd > 0 else None
+        out["roofline"]["frac_of_mfma_only_loop_random"] = out["roofline"]["achieved"] / rnd if rnd > 0 else None
+
+    # ---- the other benchmark workloads, a few passes each ----
+    if not args.no_per_config and not variant and not args.budget_mib and not args.no_compaction:
+        per = {}
+        head_line = config_line(flce, w, code, ms_per_step, compaction)
+        head_line["steps"] = args.steps
+        per[f"config{args.config}"] = dict(head_line, workload=w.name, dtype=w.dtype)
+        del X, W, t, dX, dW
+        for idx in (1, 2, 3, 4, 5):
+            if idx == args.config:
+                continue
+            wi = workloads.make_config(idx)
+            ci = flce.FLCE_BF16 if wi.dtype == "bf16" else flce.FLCE_F32
+            Xi, Wi, ti, _ = upload(wi)
+            dXi, dWi = torch.empty_like(Xi), torch.empty_like(Wi)
+
+            def step_i():
+                flce.flce_fwd_bwd(Xi, Wi, ti, wi.ignore_index, loss=loss, dX=dXi, dW=dWi)
+
+            n = 20 if idx == 1 else bsteps
+            msi, _, _ = time_steps(step_i, 2, n)
+            comp_i = flce.flce_get_row_compaction() and wi.dtype == "bf16" and wi.H % 64 == 0
+            line = config_line(flce, wi, ci, msi, comp_i)
+            line.update(workload=wi.name, dtype=wi.dtype, steps=n, loss=float(loss.item()),
+                        mfma_util_frac_of_peak=line["tflops_executed"] / MFMA_PEAK_TFLOPS[wi.dtype])
+            per[f"config{idx}"] = line
+            del Xi, Wi, ti, dXi, dWi
+            torch.cuda.empty_cache()
+        per[f"config{args.config}"]["mfma_util_frac_of_peak"] = tflops_executed / peak
+        per[f"config{args.config}"]["loss"] = loss_value
+        out["per_config"] = [per[k] | {"config": k} for k in sorted(per)]
 
     if not args.no_cpu_baseline:
         from oracle import flce_oracle
