@@ -30,6 +30,7 @@ namespace {
 constexpr int MAX_DEVICES = 64;
 constexpr int64_t MAX_DIM = (int64_t)1 << 30;      // per-dimension limit, keeps int tile math safe
 constexpr int64_t CE_ROWS_PER_LAUNCH = 65536;
+constexpr int64_t MAX_GRID_X = 0x7fffffff;        // workgroups along grid x
 constexpr size_t AUTO_BUDGET_BYTES = (size_t)1 << 30;
 constexpr int64_t AUTO_BUDGET_MIN_ROWS = 4096;
 
@@ -155,8 +156,9 @@ int launch_gemm_generic(int kind, const T* A, int64_t lda, const T* B, int64_t l
     const bool al = (K % VEC == 0) && (lda % VEC == 0) && (ldb % VEC == 0) && aligned(A, 16) &&
                     aligned(B, 16);
     const int64_t k_per = round_up((K + ksplit - 1) / ksplit, BK);
-    dim3 grid((unsigned)((N + GG_BN - 1) / GG_BN), (unsigned)((M + GG_BM - 1) / GG_BM),
-              (unsigned)ksplit);
+    const int64_t tiles = ((N + GG_BN - 1) / GG_BN) * ((M + GG_BM - 1) / GG_BM);
+    if (tiles > MAX_GRID_X) return FLCE_ERR_SHAPE;   // check_launch_limits refuses such shapes up front
+    dim3 grid((unsigned)tiles, 1, (unsigned)ksplit);
     dim3 block(GG_THREADS);
 #define GG_LAUNCH(AL, AC)                                                                       \
     hipLaunchKernelGGL((gemm_nt_generic<T, OutT, AL, AC>), grid, block, 0, s, A, lda, B, ldb, C, \
@@ -205,7 +207,9 @@ int launch_transpose(const T* in, int64_t ldin, T* out, int64_t ldout, int64_t R
                      hipStream_t s) {
     if (R <= 0 || Cc <= 0) return FLCE_OK;
     ScopedKernelTimer timer(FLCE_KIND_OTHER, s);
-    dim3 grid((unsigned)((Cc + 63) / 64), (unsigned)((R + 63) / 64));
+    const int64_t tiles = ((Cc + 63) / 64) * ((R + 63) / 64);
+    if (tiles > MAX_GRID_X) return FLCE_ERR_SHAPE;
+    dim3 grid((unsigned)tiles);
     hipLaunchKernelGGL((transpose_kernel<T>), grid, dim3(256), 0, s, in, ldin, out, ldout, (int)R,
                        (int)Cc);
     HIP_TRY(hipGetLastError());
@@ -217,24 +221,28 @@ int launch_transpose(const T* in, int64_t ldin, T* out, int64_t ldout, int64_t R
 template <typename T>
 int launch_ce_rows(T* Z, int64_t ldz, const int64_t* targets, int64_t rows, int64_t V,
                    int zero_pad, int64_t ignore_index, DeviceHeader* hdr, float* row_loss,
-                   hipStream_t s, const int* n_rows = nullptr, bool timed = true) {
+                   hipStream_t s, const int* n_rows = nullptr, bool timed = true, float* mean_out = nullptr) {
     const bool vec = aligned(Z, 16) && ((ldz * sizeof(T)) % 16 == 0);
     ScopedKernelTimer timer(timed ? FLCE_KIND_CE_ROWS : -1, s);
-    // rows from 96 KB on: the 1024-thread kernel that keeps the first 256 KB of the row in
-    // registers (measured 4.6-5.3 TB/s against 3.4-3.9 for two plain sweeps; below 96 KB
-    // the 256-thread kernel's higher occupancy wins)
-    if (vec && V * (int64_t)sizeof(T) >= 98304)
-        hipLaunchKernelGGL((ce_rows_cached_kernel<T>), dim3((unsigned)rows), dim3(RC_THREADS), 0, s, Z,
-                           ldz, targets, (int)V, zero_pad, ignore_index, hdr, row_loss, n_rows);
-    else if (vec)
-        hipLaunchKernelGGL((ce_rows_inplace_kernel<T, true>), dim3((unsigned)rows), dim3(RR_THREADS),
-                           0, s, Z, ldz, targets, (int)V, zero_pad, ignore_index, hdr, row_loss, n_rows);
+    // Rows of whole 16-byte vectors take the kernel that keeps the row in registers between
+    // its two sweeps, in the shape that fits the row: 256 threads x 12 vectors up to 48 KB,
+    // 512 x 12 up to 96 KB, 1024 x 16 beyond (the first 256 KB cached).  Measured, 4096 rows
+    // of bf16, kernel alone, TB/s of algorithmic traffic: 5.3 at 16 KB rows, 6.3-6.7 from
+    // 32 KB to 96 KB, 5.0-5.4 from 128 KB to 256 KB; two plain sweeps: 3.4-4.7.
+    const int64_t row_bytes = V * (int64_t)sizeof(T);
+#define CE_CACHED(TH, NV)                                                                              \
+    hipLaunchKernelGGL((ce_rows_cached_kernel<T, TH, NV>), dim3((unsigned)rows), dim3(TH), 0, s, Z, ldz, \
+                       targets, (int)V, zero_pad, ignore_index, hdr, row_loss, n_rows)
+    if (vec && row_bytes > 98304) CE_CACHED(RC_THREADS, RC_NV);
+    else if (vec && row_bytes > 49152) CE_CACHED(RM_THREADS, RM_NV);
+    else if (vec) CE_CACHED(RS_THREADS, RS_NV);
+#undef CE_CACHED
     else
         hipLaunchKernelGGL((ce_rows_inplace_kernel<T, false>), dim3((unsigned)rows),
                            dim3(RR_THREADS), 0, s, Z, ldz, targets, (int)V, zero_pad, ignore_index,
                            hdr, row_loss, n_rows);
     HIP_TRY(hipGetLastError());
-    hipLaunchKernelGGL(loss_accumulate_kernel, dim3(1), dim3(256), 0, s, row_loss, (int)rows, hdr);
+    hipLaunchKernelGGL(loss_accumulate_kernel, dim3(1), dim3(256), 0, s, row_loss, (int)rows, hdr, mean_out);
     HIP_TRY(hipGetLastError());
     return FLCE_OK;
 }
@@ -538,6 +546,21 @@ int check_dims(int64_t BT, int64_t H, int64_t V, int dtype) {
     return FLCE_OK;
 }
 
+// Launch-size limits of the kernels a plan uses, checked before anything is launched: the
+// guarded product and the transposes number their tiles along grid x, the row kernels and
+// the row copies take one workgroup per row of a chunk.
+int check_launch_limits(const Plan& p, int64_t H, int64_t V) {
+    auto tiles = [](int64_t r, int64_t c, int64_t t) { return ((r + t - 1) / t) * ((c + t - 1) / t); };
+    if (p.C > MAX_GRID_X) return FLCE_ERR_SHAPE;
+    const bool all_fast = p.fast_logits && p.fast_dx && p.fast_dw_full && p.fast_dw_last;
+    if (!all_fast) {
+        const int64_t worst = std::max(std::max(tiles(p.C, V, 128), tiles(V, H, 128)),
+                                       std::max(tiles(V, H, 64), tiles(p.C, V, 64)));
+        if (worst > MAX_GRID_X) return FLCE_ERR_SHAPE;
+    }
+    return FLCE_OK;
+}
+
 struct NormLayout {
     size_t off_rstd, off_partial, total;
 };
@@ -606,18 +629,14 @@ int run_ce_inplace(void* Z, const int64_t* targets, int64_t BT, int64_t V, int64
     HIP_TRY(hipGetLastError());
     for (int64_t r0 = 0; r0 < BT; r0 += step) {
         const int64_t rows = (BT - r0 < step) ? BT - r0 : step;
+        float* mean_out = (r0 + rows == BT) ? loss : nullptr;   // the last launch also writes the mean
         if (dtype == FLCE_F32)
             FLCE_TRY(launch_ce_rows<float>(static_cast<float*>(Z) + r0 * ldz, ldz, targets + r0,
-                                           rows, V, 0, ignore_index, hdr, row_loss, s, nullptr, timed));
+                                           rows, V, 0, ignore_index, hdr, row_loss, s, nullptr, timed, mean_out));
         else
             FLCE_TRY(launch_ce_rows<bf16_t>(static_cast<bf16_t*>(Z) + r0 * ldz, ldz, targets + r0,
-                                            rows, V, 0, ignore_index, hdr, row_loss, s, nullptr, timed));
+                                            rows, V, 0, ignore_index, hdr, row_loss, s, nullptr, timed, mean_out));
     }
-    HeadWeights one{};
-    one.w[0] = 1.0f;
-    hipLaunchKernelGGL(finalize_loss_kernel, dim3(1), dim3(64), 0, s, hdr, 1, one, loss,
-                       static_cast<float*>(nullptr));
-    HIP_TRY(hipGetLastError());
     return FLCE_OK;
 }
 
@@ -649,6 +668,7 @@ int flce_multihead_fwd_bwd(const void* X, const void* const* W, const int64_t* c
     if (ignore_index >= 0 && ignore_index < V) return FLCE_ERR_ARG;   // would shadow a class
 
     const Plan p = plan_for(BT, H, V, dtype);
+    FLCE_TRY(check_launch_limits(p, H, V));
     char* ws = nullptr;
     FLCE_TRY(acquire_workspace(p.total, &ws));
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -678,6 +698,7 @@ int flce_rmsnorm_fwd_bwd(const void* h, const void* gamma, float eps, const void
     if (!(eps >= 0.0f) || eps - eps != 0.0f) return FLCE_ERR_ARG;   // negative, NaN or infinite
 
     const Plan p = plan_for(BT, H, V, dtype);
+    FLCE_TRY(check_launch_limits(p, H, V));
     const NormLayout l = norm_layout(p, H);
     char* ws = nullptr;
     FLCE_TRY(acquire_workspace(l.total, &ws));

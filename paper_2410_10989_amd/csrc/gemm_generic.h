@@ -67,7 +67,9 @@ __global__ __launch_bounds__(GG_THREADS) void gemm_nt_generic(const T* __restric
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = blockIdx.y * GG_BM, n0 = blockIdx.x * GG_BN;
+    // tiles are numbered along grid x, row of tiles by row of tiles (grid y is limited to 65535)
+    const int tiles_n = (N + GG_BN - 1) / GG_BN;
+    const int m0 = (int)(blockIdx.x / tiles_n) * GG_BM, n0 = (int)(blockIdx.x % tiles_n) * GG_BN;
     // K range of this workgroup: blockIdx.z counts ranges of k_per elements (a multiple of
     // the K step), each with a result matrix of its own, split_stride elements apart
     const int k_begin = blockIdx.z * k_per;

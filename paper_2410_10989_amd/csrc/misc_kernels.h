@@ -4,14 +4,16 @@
 
 namespace flce {
 
-// out[c][r] = in[r][c] for r < R, c < Cc.  64 x 64 tile, 256 threads.
+// out[c][r] = in[r][c] for r < R, c < Cc.  64 x 64 tile, 256 threads; tiles are numbered
+// along grid x, row of tiles by row of tiles.
 template <typename T>
 __global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ in, int64_t ldin,
                                                         T* __restrict__ out, int64_t ldout, int R,
                                                         int Cc) {
     __shared__ T tile[64][64 + 2];
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+    const int tiles_c = (Cc + 63) / 64;
+    const int r0 = (int)(blockIdx.x / tiles_c) * 64, c0 = (int)(blockIdx.x % tiles_c) * 64;
 #pragma unroll 4
     for (int i = ty; i < 64; i += 4) {
         const int r = r0 + i, c = c0 + tx;

@@ -208,19 +208,26 @@ __global__ __launch_bounds__(RR_THREADS) void ce_rows_inplace_kernel(
         z[v] = ce_gradient_one<T>(z[v], v, tcol, ex, inv_n);
 }
 
-// Variant for long rows: one workgroup of 1024 threads per row keeps the first
-// 1024 * RC_NV 16-byte vectors of the row (256 KB) in registers between the two
-// sweeps, so that part of the row is read from HBM once instead of twice; what is
-// beyond is swept twice as above.  All of a thread's loads are issued before the
-// first is consumed.  16 wavefronts per CU keep the per-thread ALU phases short (a
-// variant with 4 wavefronts per CU and the whole row cached was slower than two
-// sweeps).  Measured on rows of 96 KB and more: 4.6-5.3 TB/s of algorithmic traffic
-// against 3.4-3.9 TB/s for the two-sweep kernel; shorter rows are faster there.
+// Variant that keeps the row in registers: one workgroup of THREADS threads per row holds
+// the first THREADS * NV 16-byte vectors of the row between the two sweeps, so that part
+// of the row is read from HBM once instead of twice; what is beyond is swept twice as
+// above.  All of a thread's loads are issued before the first is consumed.  Three shapes
+// are used: 256 threads x 12 vectors for rows up to 48 KB and 512 threads x 12 vectors up
+// to 96 KB, where several workgroups fit a CU and overlap one another's memory, reduction
+// and barrier phases (6.3-6.7 TB/s of algorithmic traffic on 32 .. 96 KB rows of bf16,
+// 4096 rows, kernel alone); 1024 threads x 16 vectors (256 KB) beyond, where 16 wavefronts
+// keep the per-thread ALU phases short (5.0-5.4 TB/s; a variant with 4 wavefronts per CU
+// and the whole row cached was slower than two sweeps).  At these rates the arithmetic
+// (about 16 lane operations per logit) takes as long as the memory traffic.
 constexpr int RC_THREADS = 1024;
 constexpr int RC_NV = 16;
+constexpr int RM_THREADS = 512;   // rows up to 96 KB
+constexpr int RM_NV = 12;
+constexpr int RS_THREADS = 256;   // rows up to 48 KB
+constexpr int RS_NV = 12;
 
-template <typename T>
-__global__ __launch_bounds__(RC_THREADS) void ce_rows_cached_kernel(
+template <typename T, int THREADS, int NV>
+__global__ __launch_bounds__(THREADS) void ce_rows_cached_kernel(
     T* __restrict__ Z, int64_t ldz, const int64_t* __restrict__ targets, int V, int zero_pad,
     int64_t ignore_index, const DeviceHeader* __restrict__ hdr, float* __restrict__ row_loss,
     const int* __restrict__ live) {
@@ -237,28 +244,28 @@ __global__ __launch_bounds__(RC_THREADS) void ce_rows_cached_kernel(
     const int nvec = V / VEC;                 // full vectors; the tail is handled by scalars
     u32x4* zv = reinterpret_cast<u32x4*>(z);
 
-    __shared__ MaxSum part[RC_THREADS / WAVE];
+    __shared__ MaxSum part[THREADS / WAVE];
     __shared__ float s_lse;
 
     if (tid < zero_pad) z[V + tid] = from_f32<T>(0.f);   // zero_pad < 64
     if (!valid) {                              // uniform per workgroup
         const u32x4 zero = {0u, 0u, 0u, 0u};
-        for (int i = tid; i < nvec; i += RC_THREADS) zv[i] = zero;
-        for (int v = nvec * VEC + tid; v < V; v += RC_THREADS) z[v] = from_f32<T>(0.f);
+        for (int i = tid; i < nvec; i += THREADS) zv[i] = zero;
+        for (int v = nvec * VEC + tid; v < V; v += THREADS) z[v] = from_f32<T>(0.f);
         if (tid == 0) row_loss[row] = 0.f;
         return;
     }
 
-    u32x4 keep[RC_NV];
+    u32x4 keep[NV];
 #pragma unroll
-    for (int k = 0; k < RC_NV; ++k) {
-        const int i = tid + k * RC_THREADS;
+    for (int k = 0; k < NV; ++k) {
+        const int i = tid + k * THREADS;
         if (i < nvec) keep[k] = zv[i];
     }
     MaxSum a = {-INFINITY, 0.f};
 #pragma unroll
-    for (int k = 0; k < RC_NV; ++k) {
-        const int i = tid + k * RC_THREADS;
+    for (int k = 0; k < NV; ++k) {
+        const int i = tid + k * THREADS;
         if (i < nvec) {
             float f[VEC];
             RowVec<T>::unpack(keep[k], f);
@@ -267,43 +274,50 @@ __global__ __launch_bounds__(RC_THREADS) void ce_rows_cached_kernel(
         // one vector at a time: interleaving several would spill the cached row
         __builtin_amdgcn_sched_barrier(0);
     }
-    for (int i = tid + RC_NV * RC_THREADS; i < nvec; i += RC_THREADS) {   // beyond the cache
+    for (int i = tid + NV * THREADS; i < nvec; i += THREADS) {   // beyond the cache
         float f[VEC];
         RowVec<T>::unpack(zv[i], f);
         ms_push_vec<T, VEC>(a, f);
     }
-    for (int v = nvec * VEC + tid; v < V; v += RC_THREADS) ms_push<T>(a, to_f32(z[v]));
-    const float lse = row_lse<T, RC_THREADS / WAVE>(a, z, t, row, row_loss, part, &s_lse);
+    for (int v = nvec * VEC + tid; v < V; v += THREADS) ms_push<T>(a, to_f32(z[v]));
+    const float lse = row_lse<T, THREADS / WAVE>(a, z, t, row, row_loss, part, &s_lse);
 
     const float inv_n = hdr->inv_n;
     const RowExp<T> ex(lse);
     const int tcol = (int)t;
 #pragma unroll
-    for (int k = 0; k < RC_NV; ++k) {
-        const int i = tid + k * RC_THREADS;
+    for (int k = 0; k < NV; ++k) {
+        const int i = tid + k * THREADS;
         // hide the value's history: otherwise the unpacked floats of sweep 1 are kept
         // for reuse here, which does not fit the register file and spills
         asm volatile("" : "+v"(keep[k]));
         if (i < nvec) zv[i] = ce_gradient_vec<T>(keep[k], i, tcol, ex, inv_n);
         __builtin_amdgcn_sched_barrier(0);
     }
-    for (int i = tid + RC_NV * RC_THREADS; i < nvec; i += RC_THREADS)
+    for (int i = tid + NV * THREADS; i < nvec; i += THREADS)
         zv[i] = ce_gradient_vec<T>(zv[i], i, tcol, ex, inv_n);
-    for (int v = nvec * VEC + tid; v < V; v += RC_THREADS)
+    for (int v = nvec * VEC + tid; v < V; v += THREADS)
         z[v] = ce_gradient_one<T>(z[v], v, tcol, ex, inv_n);
 }
 
 // Adds the per-row losses of one launch to the running sum, in a fixed order
-// (one workgroup, fixed strides), so repeated runs give the same bits.
+// (one workgroup, fixed strides), so repeated runs give the same bits.  With
+// `mean_out` the mean over the valid rows is written there as well (the last
+// launch of a single-head call: saves the separate finalize launch).
 __global__ __launch_bounds__(256) void loss_accumulate_kernel(const float* __restrict__ row_loss,
-                                                              int rows, DeviceHeader* hdr) {
+                                                              int rows, DeviceHeader* hdr,
+                                                              float* __restrict__ mean_out) {
     __shared__ double part[4];
     double s = 0.0;
     for (int i = threadIdx.x; i < rows; i += 256) s += (double)row_loss[i];
     s = wave_sum(s);
     if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
     __syncthreads();
-    if (threadIdx.x == 0) hdr->loss_sum += (part[0] + part[1]) + (part[2] + part[3]);
+    if (threadIdx.x == 0) {
+        const double total = hdr->loss_sum + ((part[0] + part[1]) + (part[2] + part[3]));
+        hdr->loss_sum = total;
+        if (mean_out) *mean_out = hdr->n_valid > 0 ? (float)(total / (double)hdr->n_valid) : 0.f;
+    }
 }
 
 // Counts the valid rows and resets the running loss.  Integer sum: exact in any order.
