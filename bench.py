@@ -224,6 +224,9 @@ def main():
                     help="time flce_rmsnorm_fwd_bwd: RMSNorm of raw hidden states fused in front (one head)")
     ap.add_argument("--no-mfma-loop", action="store_true",
                     help="skip the MFMA-only loop that is reported beside the roofline")
+    ap.add_argument("--mfma-loop-launches", type=int, default=160,
+                    help="launches per operand pattern of the MFMA-only loop (about 2 ms each; the socket "
+                         "power sensor needs a few seconds to settle)")
     ap.add_argument("--no-dense-leg", action="store_true", help="skip the leg with row compaction off")
     ap.add_argument("--no-per-config", action="store_true", help="skip the passes over the other four workloads")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -418,9 +421,9 @@ def main():
         # 4 x 4 fragments per K sub-step) the chip clocks far lower than on zeros.
         scratch = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
 
-        def mfma_loop(pattern, launches=160):
-            # a train of launches back to back (about 0.4 s): the clock settles within the
-            # first launches, which are left out
+        def mfma_loop(pattern, launches=max(16, args.mfma_loop_launches)):
+            # a train of launches back to back (about 0.4 s by default): the clock settles
+            # within the first launches, which are left out
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             fl = 0.0
             with PowerSampler() as ps:
@@ -438,7 +441,7 @@ def main():
             "random_operands_tflops": rnd, "zero_operands_tflops": zero,
             "random_operands_power": rnd_p, "zero_operands_power": zero_p,
             "what": "v_mfma_f32_32x32x16_bf16 on register operands, no memory traffic, 256 workgroups x 4 "
-                    "wavefronts, 152 launches of ~2-3 ms back to back after 8 to settle the clock; "
+                    f"wavefronts, {max(16, args.mfma_loop_launches) - 8} launches of ~2-3 ms back to back after 8 to settle the clock; "
                     "random = N(0,1) x N(0,0.02^2) fragments, 4 A x 4 B per 16 MFMAs"}
         for r in out["product_rooflines"].values():
             r["frac_of_mfma_only_loop_random"] = r["achieved"] / rnd if rnd > 0 else None
