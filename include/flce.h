@@ -25,7 +25,10 @@
  *    are fully overwritten (rows of dX whose target is ignored become 0).
  *  - dtype selects the storage type of X, W, dX, dW (flce_dtype).  Products
  *    accumulate in fp32; the reduction math is fp32; loss is fp32.
- *  - Any BT, H, V >= 1 (each below 2^30) are accepted.  bf16 problems with
+ *  - Any BT, H, V >= 1 (each below 2^30) are accepted, except shapes whose
+ *    kernels would exceed the launch limits (more than 2^31 - 1 tiles of 64 x 64
+ *    in one matrix on the guarded path: FLCE_ERR_SHAPE, like every argument
+ *    error before anything is launched).  bf16 problems with
  *    H % 64 == 0 run entirely on the tuned matrix-core kernel, whatever BT and V
  *    are; other H and fp32 storage run on slower, fully guarded kernels and need
  *    more workspace (transposed copies); the results meet the same bars.
@@ -211,7 +214,11 @@ FLCE_API int flce_release_workspace(void);
  * memory).  The logits chunk [C x V] is sized to fit this many bytes.  0 (the
  * default) selects the automatic rule: 1 GiB, but at least 4096 rows of logits
  * (each chunk re-reads W twice and read-modify-writes the fp32 dW partial sums,
- * which only pays off over a few thousand rows).  The getter returns the setting
+ * which only pays off over a few thousand rows); and a batch whose WHOLE logits
+ * take no more than that budget plus the V x H fp32 partial sums a chunked run
+ * needs is not chunked at all (no more memory than chunking, and faster).  A
+ * non-zero value is taken literally: chunks of at most that many bytes, one chunk
+ * only when the whole logits fit in it.  The getter returns the setting
  * (0 = automatic). */
 FLCE_API int flce_set_logits_budget_bytes(size_t bytes);
 FLCE_API size_t flce_get_logits_budget_bytes(void);
@@ -222,7 +229,9 @@ FLCE_API size_t flce_get_logits_budget_bytes(void);
  * only, and scatters dX back; the chunk's live row count stays on the device (no
  * host synchronisation).  The results are the same (dW sums the same non-zero
  * terms in other groups); the time of a chunk shrinks with its share of ignored
- * rows, in steps of the 256-row tiles.  Only problems that run entirely on the
+ * rows, in steps of the 256-row tiles.  The valid rows are dealt evenly to as few
+ * of the chunk launches as can hold them (the last ones); launches before them do
+ * no work, so a batch with many ignored rows runs fewer chunks.  Only problems that run entirely on the
  * tuned kernel are compacted.  Off: every row is projected; for batches known to
  * have no ignored row that saves the gather and scatter copies (about 0.5 % of
  * the time at V = 128K, 1 % at V = 32K). */
