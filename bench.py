@@ -336,7 +336,13 @@ def main():
                                            and compaction) else {}
     # One product launch per chunk, head and class (the K-range reduction of a cut dX product is
     # booked with it).  Executed flops of a class per step: 2 * rows projected * H * V.
-    launches_per_step = nchunks * nh
+    # (with row compaction only the last ceil(N_valid / C) chunk launches of a head do any work)
+    chunk_rows = flce.flce_chunk_rows(w.BT, w.H, w.V, code)
+    if compaction:
+        launches_per_step = sum(max(1, -(-int((x != w.ignore_index).sum().item()) // chunk_rows))
+                                for x in all_targets)
+    else:
+        launches_per_step = nchunks * nh
     class_flops_step = 2.0 * rows_projected * w.H * w.V
     rooflines = {}
     for k in gemm_kinds:
@@ -401,6 +407,12 @@ def main():
                       "chunks": flce.flce_num_chunks(bt, w.H, w.V, code)}
                      for bt in (w.BT, 4 * w.BT, 16 * w.BT)]
     out["memory_bound_any_BT_mb"] = flce.flce_workspace_bytes_max(w.H, w.V, code) / 1e6
+    # smallest BT (in steps of 256 rows) from which the workspace is smaller than the logits it
+    # stands in for: below it the whole logits simply fit and the method has nothing to save
+    bt = 256
+    while flce.flce_workspace_bytes(bt, w.H, w.V, code) >= flce.flce_full_logits_bytes(bt, w.V, code) and bt < (1 << 24):
+        bt += 256
+    out["memory_break_even_BT"] = bt
 
     # ---- dense leg: every row projected, as the paper does ----
     if compaction and not args.no_dense_leg:

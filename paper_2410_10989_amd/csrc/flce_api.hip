@@ -2,6 +2,7 @@
 // chunk loop, workspace handling, kernel launches.  Declarations and the
 // meaning of every argument are in include/flce.h.
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -44,15 +45,17 @@ struct DeviceWorkspace {
 std::mutex g_mutex;
 DeviceWorkspace g_ws[MAX_DEVICES];
 void* g_scratch_ptr[MAX_DEVICES] = {};   // device address of `scratch` on each device, once looked up
-size_t g_budget = 0;   // 0 = the automatic rule of effective_budget()
-bool g_compact = true;
+// Process-wide settings: read by every call, written by the setters (any thread).
+std::atomic<size_t> g_budget{0};   // 0 = the automatic rule of effective_budget()
+std::atomic<bool> g_compact{true};
 
 // The byte budget of the logits chunk: what the caller set, or by default 1 GiB but at
 // least 4096 rows of logits.  Every chunk costs one more pass over W and an fp32
 // read-modify-write of the dW partial sums (16 V H bytes) whatever its row count, which
 // is about 433 / C of the chunk's product time on this chip: 10 % at 4096 rows.
 size_t effective_budget(int64_t V, int dtype) {
-    if (g_budget) return g_budget;
+    const size_t set = g_budget.load();
+    if (set) return set;
     const size_t rows_bytes = (size_t)AUTO_BUDGET_MIN_ROWS * (size_t)round_up(V, 64) * elem_size(dtype);
     return rows_bytes > AUTO_BUDGET_BYTES ? rows_bytes : AUTO_BUDGET_BYTES;
 }
@@ -63,7 +66,7 @@ size_t effective_budget(int64_t V, int dtype) {
 // than chunking would; it is also the faster plan.
 size_t single_chunk_bytes(int64_t H, int64_t V, int dtype) {
     const size_t b = effective_budget(V, dtype);
-    if (g_budget || dtype == FLCE_F32) return b;
+    if (g_budget.load() || dtype == FLCE_F32) return b;
     return b + (size_t)V * (size_t)H * sizeof(float);
 }
 
@@ -78,15 +81,19 @@ struct TimingRecord {
     int kind;
 };
 constexpr int MAX_TIMING_RECORDS = 8192;
-bool g_timing_on = false;
-std::vector<TimingRecord> g_records;
+std::atomic<bool> g_timing_on{false};
+std::vector<TimingRecord> g_records;   // guarded by g_mutex
 
 struct ScopedKernelTimer {
     hipStream_t stream;
     bool active = false;
     TimingRecord rec{};
     ScopedKernelTimer(int kind, hipStream_t s) : stream(s) {   // kind < 0: never timed
-        if (kind < 0 || !g_timing_on || (int)g_records.size() >= MAX_TIMING_RECORDS) return;
+        if (kind < 0 || !g_timing_on.load()) return;
+        {
+            std::lock_guard<std::mutex> lock(g_mutex);
+            if ((int)g_records.size() >= MAX_TIMING_RECORDS) return;
+        }
         if (hipEventCreate(&rec.start) != hipSuccess) return;
         if (hipEventCreate(&rec.stop) != hipSuccess) {
             (void)hipEventDestroy(rec.start);
@@ -98,6 +105,7 @@ struct ScopedKernelTimer {
     ~ScopedKernelTimer() {
         if (!active) return;
         (void)hipEventRecord(rec.stop, stream);
+        std::lock_guard<std::mutex> lock(g_mutex);
         g_records.push_back(rec);
     }
 };
@@ -812,20 +820,18 @@ int flce_release_workspace(void) {
 }
 
 int flce_set_logits_budget_bytes(size_t bytes) {
-    std::lock_guard<std::mutex> lock(g_mutex);
-    g_budget = bytes;
+    g_budget.store(bytes);
     return FLCE_OK;
 }
 
-size_t flce_get_logits_budget_bytes(void) { return g_budget; }
+size_t flce_get_logits_budget_bytes(void) { return g_budget.load(); }
 
 int flce_set_row_compaction(int on) {
-    std::lock_guard<std::mutex> lock(g_mutex);
-    g_compact = (on != 0);
+    g_compact.store(on != 0);
     return FLCE_OK;
 }
 
-int flce_get_row_compaction(void) { return g_compact ? 1 : 0; }
+int flce_get_row_compaction(void) { return g_compact.load() ? 1 : 0; }
 
 int64_t flce_chunk_rows(int64_t BT, int64_t H, int64_t V, int dtype) {
     if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
@@ -869,8 +875,7 @@ int flce_mfma_ceiling_launch(int pattern, int workgroups, int iters, float std_b
 }
 
 int flce_timing_enable(int on) {
-    std::lock_guard<std::mutex> lock(g_mutex);
-    g_timing_on = (on != 0);
+    g_timing_on.store(on != 0);
     return FLCE_OK;
 }
 

@@ -68,6 +68,26 @@ def test_dx_is_cut_along_k_when_the_tile_count_leaves_a_poor_last_round():
     check_full(workloads.make(4352, 4096, 8192, "bf16", ignore=("iid", 0.1), seed=272, name="tail"))
 
 
+@pytest.mark.parametrize("ignore_frac", [0.0, 0.4, 0.75])
+def test_dx_k_ranges_follow_the_live_row_count(ignore_frac):
+    # 3 x 1 output tiles of dX, K = V = 16384 (256 K steps): a full chunk is cut into 4 K
+    # ranges; with rows ignored the device picks fewer ranges for the live tiles (2 tile rows:
+    # 3 ranges, 1 tile row: 4 again), sums their partial results in a fixed order, and the
+    # result matches the oracle element by element; without compaction the host's choice runs
+    import paper_2410_10989_amd as flce
+    assert flce.flce_dx_k_ranges(600, 256, 16384, flce.FLCE_BF16) == 4
+    w = workloads.make(600, 256, 16384, "bf16", ignore=("iid", ignore_frac) if ignore_frac else ("none",),
+                       seed=4242 + int(100 * ignore_frac), name="k_ranges")
+    on = check_full(w)
+    try:
+        flce.flce_set_row_compaction(False)
+        off = check_full(w)
+    finally:
+        flce.flce_set_row_compaction(True)
+    err = (on[1].float() - off[1].float()).abs().max().item()
+    assert err <= 2.0 ** -7 * off[1].float().abs().max().item()   # other K ranges: other rounding, not more
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_several_chunks_with_ragged_last_chunk(dtype):
     # A budget of 256 rows of logits forces 3 chunks (256, 256, 1 rows); the
