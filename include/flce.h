@@ -107,6 +107,32 @@ FLCE_API int flce_fwd_bwd_ex(const void* X, const void* W, const int64_t* target
                     unsigned flags, void* stream);
 
 /*
+ * The same call with its settings passed along instead of taken from the
+ * process-wide setters below (flce_set_logits_budget_bytes,
+ * flce_set_row_compaction), for callers that run several configurations side by
+ * side or from several threads.  (Paper section 3.2, FLCE paragraph: the chunk
+ * size is the method's one tuning knob.)
+ *   size                 must be sizeof(flce_options) (FLCE_ERR_ARG otherwise)
+ *   logits_budget_bytes  bytes one chunk of logits may take, 0 = the automatic rule
+ *   row_compaction       0 or 1
+ *   flags                FLCE_SKIP_*
+ * flce_default_options fills a struct with the current process-wide settings and
+ * flags = 0.  opt == NULL means exactly that.  flce_workspace_bytes_opt is
+ * flce_workspace_bytes for such a call (0 for bad arguments).
+ */
+typedef struct {
+    size_t size;
+    size_t logits_budget_bytes;
+    int row_compaction;
+    unsigned flags;
+} flce_options;
+FLCE_API void flce_default_options(flce_options* opt);
+FLCE_API int flce_fwd_bwd_opt(const void* X, const void* W, const int64_t* targets, int64_t BT, int64_t H,
+                     int64_t V, int64_t ignore_index, int dtype, float* loss, void* dX, void* dW,
+                     const flce_options* opt, void* stream);
+FLCE_API size_t flce_workspace_bytes_opt(int64_t BT, int64_t H, int64_t V, int dtype, const flce_options* opt);
+
+/*
  * Several output heads on the same hidden states (paper section 4.2, Medusa
  * paragraph: extra decoding heads, head j trained to predict the token j + 1
  * positions further on, each with a cross-entropy loss of its own, all sharing

@@ -39,6 +39,9 @@ def lib() -> ctypes.CDLL:
         sigs = {
             "flce_fwd_bwd": ([p, p, p, i64, i64, i64, i64, ci, p, p, p, p], ci),
             "flce_fwd_bwd_ex": ([p, p, p, i64, i64, i64, i64, ci, p, p, p, u, p], ci),
+            "flce_fwd_bwd_opt": ([p, p, p, i64, i64, i64, i64, ci, p, p, p, p, p], ci),
+            "flce_default_options": ([p], None),
+            "flce_workspace_bytes_opt": ([i64, i64, i64, ci, p], sz),
             "flce_multihead_fwd_bwd": ([p, p, p, p, ci, i64, i64, i64, i64, ci, p, p, p, p, u, p], ci),
             "flce_rmsnorm_fwd_bwd": ([p, p, ctypes.c_float, p, p, i64, i64, i64, i64, ci, p, p, p, p, u, p], ci),
             "flce_rmsnorm_workspace_bytes": ([i64, i64, i64, ci], sz),
@@ -133,6 +136,53 @@ def flce_fwd_bwd(X, W, targets, ignore_index=-100, loss=None, dX=None, dW=None, 
                                    _stream_handle(stream))
     _check(st, "flce_fwd_bwd")
     return loss, dX, dW
+
+
+class FlceOptions(ctypes.Structure):
+    """flce_options of include/flce.h."""
+    _fields_ = [("size", ctypes.c_size_t), ("logits_budget_bytes", ctypes.c_size_t),
+                ("row_compaction", ctypes.c_int), ("flags", ctypes.c_uint)]
+
+
+def flce_options(logits_budget_bytes=None, row_compaction=None, flags=0) -> FlceOptions:
+    """The process-wide settings (flce_default_options) with the given fields replaced."""
+    o = FlceOptions()
+    lib().flce_default_options(ctypes.byref(o))
+    if logits_budget_bytes is not None:
+        o.logits_budget_bytes = int(logits_budget_bytes)
+    if row_compaction is not None:
+        o.row_compaction = 1 if row_compaction else 0
+    o.flags = int(flags)
+    return o
+
+
+def flce_fwd_bwd_opt(X, W, targets, options: FlceOptions, ignore_index=-100, loss=None, dX=None,
+                     dW=None, stream=None):
+    """flce_fwd_bwd with its settings passed along (see flce_options)."""
+    code = _dtype_code(X)
+    if W.dtype != X.dtype or targets.dtype != torch.int64:
+        raise TypeError("X and W must have the same dtype, targets must be int64")
+    if X.dim() != 2 or W.dim() != 2 or X.shape[1] != W.shape[1] or targets.shape != (X.shape[0],):
+        raise ValueError("expected X [BT, H], W [V, H], targets [BT]")
+    BT, H = X.shape
+    V = W.shape[0]
+    if loss is None:
+        loss = torch.empty((), dtype=torch.float32, device=X.device)
+    if dX is None and not (options.flags & SKIP_DX):
+        dX = torch.empty_like(X)
+    if dW is None and not (options.flags & SKIP_DW):
+        dW = torch.empty_like(W)
+    with torch.cuda.device(X.device):
+        st = lib().flce_fwd_bwd_opt(_dev_ptr(X, "X"), _dev_ptr(W, "W"), _dev_ptr(targets, "targets"),
+                                    BT, H, V, int(ignore_index), code, _dev_ptr(loss, "loss"),
+                                    _dev_ptr(dX, "dX"), _dev_ptr(dW, "dW"), ctypes.byref(options),
+                                    _stream_handle(stream))
+    _check(st, "flce_fwd_bwd_opt")
+    return loss, dX, dW
+
+
+def flce_workspace_bytes_opt(BT, H, V, dtype, options: FlceOptions) -> int:
+    return int(lib().flce_workspace_bytes_opt(BT, H, V, _DTYPES.get(dtype, dtype), ctypes.byref(options)))
 
 
 def flce_multihead_fwd_bwd(X, Ws, targets, weights=None, ignore_index=-100, loss=None,

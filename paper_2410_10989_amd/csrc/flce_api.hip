@@ -49,13 +49,20 @@ void* g_scratch_ptr[MAX_DEVICES] = {};   // device address of `scratch` on each 
 std::atomic<size_t> g_budget{0};   // 0 = the automatic rule of effective_budget()
 std::atomic<bool> g_compact{true};
 
+// What a call's plan depends on besides the shape: the process-wide settings, or the
+// options a caller passes with the call.
+struct Settings {
+    size_t budget;   // 0 = the automatic rule
+    bool compact;
+};
+Settings global_settings() { return {g_budget.load(), g_compact.load()}; }
+
 // The byte budget of the logits chunk: what the caller set, or by default 1 GiB but at
 // least 4096 rows of logits.  Every chunk costs one more pass over W and an fp32
 // read-modify-write of the dW partial sums (16 V H bytes) whatever its row count, which
 // is about 433 / C of the chunk's product time on this chip: 10 % at 4096 rows.
-size_t effective_budget(int64_t V, int dtype) {
-    const size_t set = g_budget.load();
-    if (set) return set;
+size_t effective_budget(const Settings& st, int64_t V, int dtype) {
+    if (st.budget) return st.budget;
     const size_t rows_bytes = (size_t)AUTO_BUDGET_MIN_ROWS * (size_t)round_up(V, 64) * elem_size(dtype);
     return rows_bytes > AUTO_BUDGET_BYTES ? rows_bytes : AUTO_BUDGET_BYTES;
 }
@@ -64,15 +71,18 @@ size_t effective_budget(int64_t V, int dtype) {
 // the budget.  Automatic rule: the chunk budget plus the fp32 dW partial sums that only
 // a chunked run needs (bf16 storage), i.e. one chunk whenever that takes no more memory
 // than chunking would; it is also the faster plan.
-size_t single_chunk_bytes(int64_t H, int64_t V, int dtype) {
-    const size_t b = effective_budget(V, dtype);
-    if (g_budget.load() || dtype == FLCE_F32) return b;
+size_t single_chunk_bytes(const Settings& st, int64_t H, int64_t V, int dtype) {
+    const size_t b = effective_budget(st, V, dtype);
+    if (st.budget || dtype == FLCE_F32) return b;
     return b + (size_t)V * (size_t)H * sizeof(float);
 }
 
+Plan plan_for(const Settings& st, int64_t BT, int64_t H, int64_t V, int dtype, bool worst_case_bt = false) {
+    return make_plan(BT, H, V, dtype, effective_budget(st, V, dtype), worst_case_bt, st.compact,
+                     single_chunk_bytes(st, H, V, dtype));
+}
 Plan plan_for(int64_t BT, int64_t H, int64_t V, int dtype, bool worst_case_bt = false) {
-    return make_plan(BT, H, V, dtype, effective_budget(V, dtype), worst_case_bt, g_compact,
-                     single_chunk_bytes(H, V, dtype));
+    return plan_for(global_settings(), BT, H, V, dtype, worst_case_bt);
 }
 
 // ---- optional per-kernel timing (benchmarks only) ----
@@ -648,14 +658,11 @@ int run_ce_inplace(void* Z, const int64_t* targets, int64_t BT, int64_t V, int64
     return FLCE_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-int flce_multihead_fwd_bwd(const void* X, const void* const* W, const int64_t* const* targets,
-                           const float* weights, int n_heads, int64_t BT, int64_t H, int64_t V,
-                           int64_t ignore_index, int dtype, float* loss, float* head_losses, void* dX,
-                           void* const* dW, unsigned flags, void* stream) {
+// flce_multihead_fwd_bwd with the settings given (the process-wide ones, or a call's options)
+int multihead_fwd_bwd(const Settings& st, const void* X, const void* const* W, const int64_t* const* targets,
+                      const float* weights, int n_heads, int64_t BT, int64_t H, int64_t V,
+                      int64_t ignore_index, int dtype, float* loss, float* head_losses, void* dX,
+                      void* const* dW, unsigned flags, void* stream) {
     FLCE_TRY(check_dims(BT, H, V, dtype));
     if (n_heads < 1 || n_heads > MAX_HEADS) return FLCE_ERR_ARG;
     if (flags & ~(unsigned)(FLCE_SKIP_DX | FLCE_SKIP_DW)) return FLCE_ERR_ARG;
@@ -675,7 +682,7 @@ int flce_multihead_fwd_bwd(const void* X, const void* const* W, const int64_t* c
     }
     if (ignore_index >= 0 && ignore_index < V) return FLCE_ERR_ARG;   // would shadow a class
 
-    const Plan p = plan_for(BT, H, V, dtype);
+    const Plan p = plan_for(st, BT, H, V, dtype);
     FLCE_TRY(check_launch_limits(p, H, V));
     char* ws = nullptr;
     FLCE_TRY(acquire_workspace(p.total, &ws));
@@ -687,6 +694,60 @@ int flce_multihead_fwd_bwd(const void* X, const void* const* W, const int64_t* c
     return run_heads<bf16_t>(static_cast<const bf16_t*>(X), W, targets, weights, n_heads, BT, H, V,
                              ignore_index, loss, head_losses, static_cast<bf16_t*>(dX), dW, flags, p,
                              ws, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+int flce_multihead_fwd_bwd(const void* X, const void* const* W, const int64_t* const* targets,
+                           const float* weights, int n_heads, int64_t BT, int64_t H, int64_t V,
+                           int64_t ignore_index, int dtype, float* loss, float* head_losses, void* dX,
+                           void* const* dW, unsigned flags, void* stream) {
+    return multihead_fwd_bwd(global_settings(), X, W, targets, weights, n_heads, BT, H, V, ignore_index,
+                             dtype, loss, head_losses, dX, dW, flags, stream);
+}
+
+void flce_default_options(flce_options* opt) {
+    if (!opt) return;
+    const Settings st = global_settings();
+    opt->size = sizeof(flce_options);
+    opt->logits_budget_bytes = st.budget;
+    opt->row_compaction = st.compact ? 1 : 0;
+    opt->flags = 0u;
+}
+
+// The settings a call's options stand for; FLCE_ERR_ARG for a struct this library cannot read.
+static int settings_from(const flce_options* opt, Settings* st, unsigned* flags) {
+    *st = global_settings();
+    *flags = 0u;
+    if (!opt) return FLCE_OK;
+    if (opt->size != sizeof(flce_options)) return FLCE_ERR_ARG;
+    if (opt->row_compaction != 0 && opt->row_compaction != 1) return FLCE_ERR_ARG;
+    st->budget = opt->logits_budget_bytes;
+    st->compact = opt->row_compaction != 0;
+    *flags = opt->flags;
+    return FLCE_OK;
+}
+
+int flce_fwd_bwd_opt(const void* X, const void* W, const int64_t* targets, int64_t BT, int64_t H,
+                     int64_t V, int64_t ignore_index, int dtype, float* loss, void* dX, void* dW,
+                     const flce_options* opt, void* stream) {
+    Settings st;
+    unsigned flags;
+    FLCE_TRY(settings_from(opt, &st, &flags));
+    const void* Ws[1] = {W};
+    const int64_t* ts[1] = {targets};
+    void* dWs[1] = {dW};
+    return multihead_fwd_bwd(st, X, Ws, ts, nullptr, 1, BT, H, V, ignore_index, dtype, loss, nullptr, dX,
+                             dWs, flags, stream);
+}
+
+size_t flce_workspace_bytes_opt(int64_t BT, int64_t H, int64_t V, int dtype, const flce_options* opt) {
+    Settings st;
+    unsigned flags;
+    if (check_dims(BT, H, V, dtype) != FLCE_OK || settings_from(opt, &st, &flags) != FLCE_OK) return 0;
+    return plan_for(st, BT, H, V, dtype).total;
 }
 
 int flce_rmsnorm_fwd_bwd(const void* h, const void* gamma, float eps, const void* W,

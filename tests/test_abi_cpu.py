@@ -160,3 +160,33 @@ def test_binding_refuses_cpu_tensors():
     t = torch.zeros(4, dtype=torch.int64)
     with pytest.raises(ValueError):
         flce.flce_fwd_bwd(X, W, t, loss=torch.zeros(()), dX=X.clone(), dW=W.clone())
+
+
+def test_options_passed_with_the_call_plan_like_the_setters():
+    code = flce.FLCE_BF16
+    H, V = 4096, 128256
+    o = flce.flce_options()
+    assert o.size == ctypes.sizeof(flce.FlceOptions) and o.logits_budget_bytes == 0 and o.row_compaction == 1
+    assert flce.flce_workspace_bytes_opt(8192, H, V, code, o) == flce.flce_workspace_bytes(8192, H, V, code)
+    lit = flce.flce_options(logits_budget_bytes=1 << 30)          # a budget taken literally: two chunks
+    old = flce.flce_get_logits_budget_bytes()
+    try:
+        flce.flce_set_logits_budget_bytes(1 << 30)
+        want = flce.flce_workspace_bytes(8192, H, V, code)
+    finally:
+        flce.flce_set_logits_budget_bytes(old)
+    assert flce.flce_workspace_bytes_opt(8192, H, V, code, lit) == want != flce.flce_workspace_bytes(8192, H, V, code)
+    assert flce.flce_get_logits_budget_bytes() == old              # the call's options leave the process-wide ones alone
+    bad = flce.flce_options()
+    bad.size = 8
+    assert flce.flce_workspace_bytes_opt(8192, H, V, code, bad) == 0
+    L = flce.lib()
+    buf = (ctypes.c_char * 4096)()
+    a = ctypes.addressof(buf)
+    a += (-a) % 256
+    assert L.flce_fwd_bwd_opt(a, a + 256, a + 512, 4, 8, 16, -100, 1, a + 768, a + 1024, a + 1280,
+                              ctypes.byref(bad), None) == 7
+    bad = flce.flce_options()
+    bad.row_compaction = 5
+    assert L.flce_fwd_bwd_opt(a, a + 256, a + 512, 4, 8, 16, -100, 1, a + 768, a + 1024, a + 1280,
+                              ctypes.byref(bad), None) == 7

@@ -406,3 +406,33 @@ def test_mfma_only_loop_runs_and_counts_its_flops():
     assert torch.isfinite(out).all() and (out != 0).any()
     with pytest.raises(flce.FlceError):
         flce.flce_mfma_ceiling_launch(2, 9, 10, 0.02, out)       # out too small
+
+
+def test_options_passed_with_the_call_equal_the_setters():
+    # three chunks without row compaction through flce_fwd_bwd_opt: the same bits as the same
+    # settings made through the process-wide setters, which the call leaves untouched
+    import paper_2410_10989_amd as flce
+    w = workloads.make(700, 128, 1536, "bf16", ignore=("iid", 0.2), seed=31, name="options")
+    X, W, t = upload(w)
+    budget = 256 * 1536 * 2
+    o = flce.flce_options(logits_budget_bytes=budget, row_compaction=False)
+    loss_o, dX_o, dW_o = flce.flce_fwd_bwd_opt(X, W, t, o, w.ignore_index)
+    torch.cuda.synchronize()
+    assert flce.flce_get_logits_budget_bytes() == 0 and flce.flce_get_row_compaction()
+    try:
+        flce.flce_set_logits_budget_bytes(budget)
+        flce.flce_set_row_compaction(False)
+        assert flce.flce_num_chunks(w.BT, w.H, w.V, flce.FLCE_BF16) == 3
+        loss_s, dX_s, dW_s = run_gpu(w)
+    finally:
+        flce.flce_set_logits_budget_bytes(0)
+        flce.flce_set_row_compaction(True)
+    assert loss_o.item() == loss_s
+    assert torch.equal(dX_o.view(torch.int16), dX_s.view(torch.int16))
+    assert torch.equal(dW_o.view(torch.int16), dW_s.view(torch.int16))
+    ref = oracle.flce(w.X, w.W, w.targets, w.ignore_index)
+    assert_close("dW", to_host(dW_o), ref.dW, TOL["bf16"][1])
+    skip = flce.flce_options(flags=flce.SKIP_DX)
+    loss_k, dX_k, dW_k = flce.flce_fwd_bwd_opt(X, W, t, skip, w.ignore_index)
+    torch.cuda.synchronize()
+    assert dX_k is None and abs(loss_k.item() - ref.loss) <= TOL["bf16"][0] * abs(ref.loss)
