@@ -101,7 +101,40 @@ struct FGArgs {
     // taken as zero (not read) unless launch > *first_live.
     const int* first_live;
     int launch;
+    // Tiles of the last, partly filled round cut along K (see fg_tail_plan): from position
+    // tail_begin of an XCD's tile span on, the next tail_r tiles are computed as tail_s K
+    // ranges each by tail_r * tail_s workgroups, which write fp32 partial blocks of 256 x
+    // 256 to tail_part; fg_tail_reduce_kernel adds them up and writes C.  tail_s <= 1: off.
+    int tail_begin, tail_r, tail_s;
+    float* tail_part;
 };
+
+// A launch of one workgroup per tile runs in rounds of as many tiles as the chip has CUs
+// (one tile per CU at a time: a tile takes the whole LDS).  When the last round holds only
+// r <= 16 tiles per XCD, two thirds or more of the CUs would idle through it, so each of
+// those tiles is cut into s = 32 / r K ranges instead (at most 8, each at least 16 K steps
+// long): the round takes 1 / s of a tile's time plus a small reduction.  Returns s (1 = the
+// launch is left as it is); `total` = tiles of the launch, ksteps = K steps per tile.
+struct FgTailPlan {
+    int begin, r, s;
+};
+inline FgTailPlan fg_tail_plan(int64_t total, int64_t ksteps) {
+    constexpr int CUS_PER_XCD = 32;
+    FgTailPlan t{0, 0, 1};
+    const int64_t per_xcd = (total + FG_XCDS - 1) / FG_XCDS;
+    const int r = (int)(per_xcd % CUS_PER_XCD);
+    if (per_xcd < CUS_PER_XCD || r == 0 || r > CUS_PER_XCD / 2) return t;
+    int s = CUS_PER_XCD / r;
+    if (s > 8) s = 8;
+    while (s > 1 && ksteps / s < 16) --s;
+    if (s <= 1) return t;
+    t.begin = (int)(per_xcd - r);
+    t.r = r;
+    t.s = s;
+    return t;
+}
+constexpr int FG_TAIL_MAX_BLOCKS = FG_XCDS * 32;   // partial blocks a launch can need (r * s <= 32 per XCD)
+constexpr size_t FG_TAIL_BLOCK_FLOATS = (size_t)FG_BM * FG_BN;
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
@@ -275,6 +308,194 @@ __device__ __forceinline__ void fg_zero(FgRaw<true>& r) {
 template <typename InT> struct FgInSize { static constexpr int value = (int)sizeof(InT); };
 template <> struct FgInSize<void> { static constexpr int value = 4; };
 
+// Writes a workgroup's 256 x 256 tile of fp32 accumulators out.  The MFMAs are fed the B
+// fragment first and the A fragment second, so accumulator register g of lane l is ROW
+// l%32, column 8*(g/4)+4*(l/32)+g%4 of its 32 x 32 tile: four consecutive columns per group
+// of four registers.  Written straight from the registers, a store instruction would touch
+// 32 different rows.  The memory pipe's cost is per instruction (about 9 cycles of the CU's
+// address unit per wavefront-wide store, whatever it carries: measured), so the tile goes
+// through LDS instead, which is free by then: each wavefront stages 32 rows x 128 columns of
+// its 128 x 128 sub-tile as fp32 in its own LDS region, reads them back row-major, 16 bytes
+// of output per lane (4 fp32 or 8 bf16 consecutive columns), adds the addend (loaded with
+// the same wide, row-contiguous accesses, one pass ahead) and stores 16 bytes per lane: 16
+// or 8 times fewer memory instructions, each writing whole row segments.  Loads and stores go
+// through buffer descriptors that cover the tile's valid rows (rows past them are dropped by
+// the range check).  OutT: element type of C; InT: of the addend (void: none).
+template <typename OutT, typename InT>
+struct FgOut {
+    static constexpr bool HAS_IN = !std::is_void<InT>::value;
+    static constexpr int IS = FgInSize<InT>::value;
+    static constexpr int ES = (int)sizeof(OutT);
+    static constexpr int EW = 16 / ES;                 // output elements per lane and access: 4 or 8
+    static constexpr int LANES_PER_ROW = 128 / EW;     // 32 or 16
+    static constexpr int ROWS_PER_ACCESS = 64 / LANES_PER_ROW;   // rows one wavefront-wide access covers: 2 or 4
+    static constexpr int PITCH = 128 + 4;              // fp32 words per staged row: 16 lanes' 16-byte writes of one column group hit 64 different banks
+    static constexpr int NACC = 32 / ROWS_PER_ACCESS;  // accesses per 32-row pass: 16 or 8
+    static constexpr int INW = HAS_IN ? EW * IS / 4 : 1;   // dwords of addend per lane and access
+
+    __amdgpu_buffer_rsrc_t rsrc_c, rsrc_in;
+    int ldc, ldcin, uwm, colw, orow, ocol, lane_off, lane_off_in, frow, fhalf;
+    bool col_ok;
+    float* stage;
+    // Two buffers: a pass's addend is requested one pass ahead, the first one before the last
+    // MFMAs of the K loop, so that the memory latency (a few thousand cycles: the addend comes
+    // from HBM) is not waited for in every pass.
+    uint32_t old2[HAS_IN ? 2 : 1][NACC][INW];
+
+    // c_tile / cin_tile: first element of the tile's first row (column 0 of the matrix);
+    // rows: valid rows of the tile; col0: the tile's first column; n_cols: columns of the matrix
+    // (written in groups of EW: its rows must be allocated up to n_cols rounded up to EW).
+    __device__ __forceinline__ void init(void* c_tile, int ldc_, const void* cin_tile, int ldcin_, bool use_in,
+                                         int rows, int col0, int n_cols, unsigned char* smem, int lane,
+                                         int uwave, int uwm_, int uwn) {
+        ldc = ldc_;
+        ldcin = ldcin_;
+        uwm = uwm_;
+        frow = lane & 31;
+        fhalf = lane >> 5;
+        rsrc_c = fg_make_rsrc(c_tile, (uint32_t)rows * (uint32_t)ldc * (uint32_t)ES);
+        rsrc_in = rsrc_c;
+        if constexpr (HAS_IN)   // a range of zero bytes makes every addend load return zero without touching memory
+            rsrc_in = fg_make_rsrc(cin_tile, use_in ? (uint32_t)rows * (uint32_t)ldcin * (uint32_t)IS : 0u);
+        stage = reinterpret_cast<float*>(smem + uwave * (FG_LDS_BYTES / 4));   // 40 KB per wavefront
+        // output mapping of the lane: row (inside a group of ROWS_PER_ACCESS) and first column
+        orow = lane / LANES_PER_ROW;
+        ocol = (lane % LANES_PER_ROW) * EW;
+        colw = col0 + uwn * 128;                       // first column of the wavefront's sub-tile
+        col_ok = colw + ocol < ((n_cols + EW - 1) / EW) * EW;
+        lane_off = (orow * ldc + ocol) * ES;
+        lane_off_in = (orow * ldcin + ocol) * IS;
+    }
+
+    // Addend of pass `pass` (rows 32 pass .. + 31 of the wavefront's sub-tile) into buffer B.
+    template <int B>
+    __device__ __forceinline__ void load_addend(int pass) {
+        if constexpr (HAS_IN) {
+            const int row0 = uwm * 128 + pass * 32;
+#pragma unroll
+            for (int k = 0; k < NACC; ++k) {
+                const int soff = ((row0 + k * ROWS_PER_ACCESS) * ldcin + colw) * IS;
+                if constexpr (INW == 4) {
+                    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc_in, lane_off_in, soff, 0);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) old2[B][k][e] = v[e];
+                } else if constexpr (INW == 8) {
+                    const u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(rsrc_in, lane_off_in, soff, 0);
+                    const u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(rsrc_in, lane_off_in + 16, soff, 0);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        old2[B][k][e] = v0[e];
+                        old2[B][k][4 + e] = v1[e];
+                    }
+                } else {   // 8 bf16 = 4 dwords, or 4 bf16 = 2 dwords
+                    static_assert(INW == 2, "addend width");
+                    const auto v = __builtin_amdgcn_raw_buffer_load_b64(rsrc_in, lane_off_in, soff, 0);
+                    old2[B][k][0] = v[0];
+                    old2[B][k][1] = v[1];
+                }
+            }
+        }
+    }
+
+    // The four passes; load_addend<0>(0) has been issued before.
+    __device__ __forceinline__ void write(f32x16 (&acc)[4][4]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {                          // pass: rows 32 i .. 32 i + 31 of the sub-tile
+            const int row0 = uwm * 128 + i * 32;
+            // the next pass's addend is requested before this pass is staged: it arrives while this
+            // pass goes through LDS
+            if (i == 0) load_addend<1>(1);
+            if (i == 1) load_addend<0>(2);
+            if (i == 2) load_addend<1>(3);
+            uint32_t (&old)[NACC][INW] = old2[HAS_IN ? (i & 1) : 0];
+            // stage the pass: the lane holds row frow and, per group of four registers, the four
+            // consecutive columns 32 j + 8 (g/4) + 4 fhalf .. + 3: one 16-byte LDS write per group
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    // read the elements into scalars first: a bit_cast applied directly
+                    // to an accumulator vector element is miscompiled by this toolchain
+                    const float v0 = acc[i][j][4 * g4], v1 = acc[i][j][4 * g4 + 1], v2 = acc[i][j][4 * g4 + 2],
+                                v3 = acc[i][j][4 * g4 + 3];
+                    const f32x4 q = {v0, v1, v2, v3};
+                    *reinterpret_cast<f32x4*>(stage + frow * PITCH + 32 * j + 8 * g4 + 4 * fhalf) = q;
+                }
+            // The region is private to the wavefront and LDS executes a wavefront's accesses in
+            // order: no workgroup barrier is needed, only that the compiler keeps the order (a
+            // barrier of the usual kind would also wait for the global stores of the previous
+            // pass to be acknowledged: measured 1 000 cycles per pass).
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int k = 0; k < NACC; ++k) {
+                const float* src = stage + (k * ROWS_PER_ACCESS + orow) * PITCH + ocol;
+                float v[EW];
+#pragma unroll
+                for (int e = 0; e < EW; e += 4) {
+                    const f32x4 q = *reinterpret_cast<const f32x4*>(src + e);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) v[e + u] = q[u];
+                }
+                if constexpr (HAS_IN) {
+#pragma unroll
+                    for (int e = 0; e < EW; ++e) {
+                        if constexpr (IS == 4) v[e] += __uint_as_float(old[k][e]);
+                        else v[e] += __uint_as_float((e & 1) ? (old[k][e >> 1] & 0xffff0000u) : (old[k][e >> 1] << 16));
+                    }
+                }
+                const int soff = ((row0 + k * ROWS_PER_ACCESS) * ldc + colw) * ES;
+                u32x4 out;
+                if constexpr (ES == 4) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) out[e] = __float_as_uint(v[e]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const bf16x2 p2 = {from_f32<bf16_t>(v[2 * e]), from_f32<bf16_t>(v[2 * e + 1])};
+                        out[e] = __builtin_bit_cast(uint32_t, p2);
+                    }
+                }
+                if (col_ok) __builtin_amdgcn_raw_buffer_store_b128(out, rsrc_c, lane_off, soff, 0);
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next pass rewrites the region
+        }
+    }
+};
+
+// What a launch's device-side values resolve to (shared by the product kernel and the
+// reduction of its tail blocks).
+struct FgResolved {
+    int M, K, ksplit;
+    bool skip, use_in;
+};
+__device__ __forceinline__ FgResolved fg_resolve(const FGArgs& a, bool has_in) {
+    FgResolved r{a.M, a.K, a.ksplit, false, has_in};
+    if (a.first_live) {
+        const int fl = *a.first_live;   // uniform: a scalar load
+        r.skip = a.launch < fl;
+        r.use_in = has_in && a.launch > fl;
+    }
+    if (a.dyn_rows) {
+        const int n = *a.dyn_rows;
+        if (a.dyn_is_k) r.K = min(r.K, n); else r.M = min(r.M, n);
+    }
+    if (a.dyn_ksplit) r.ksplit = min(r.ksplit, max(1, *a.dyn_ksplit));
+    return r;
+}
+
+// Tile number `seq` of the grouped order (FG_GROUP_M tile rows at a time, column by column
+// inside a group) -> first row and column of the tile.
+__device__ __forceinline__ void fg_tile_origin(int seq, int tiles_m, int tiles_n, int& m0, int& n0) {
+    const int group_size = FG_GROUP_M * tiles_n;
+    const int grp = seq / group_size;
+    const int first_m = grp * FG_GROUP_M;
+    const int gm = min(FG_GROUP_M, tiles_m - first_m);
+    const int rem = seq - grp * group_size;
+    m0 = (first_m + rem % gm) * FG_BM;
+    n0 = (rem / gm) * FG_BN;
+}
+
+
 // InT: element type of the addend Cin (float or bf16_t), void for no addend.
 template <typename OutT, typename InT, bool A_KM, bool B_KM>
 __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
@@ -286,19 +507,10 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
     const int wm = wave >> 1, wn = wave & 1;
 
     // ---- workgroup id -> (K range, tile) (XCD aware, grouped order) ----
-    int M = a.M, K = a.K, ksplit = a.ksplit;
-    bool use_in = HAS_IN;
-    if (a.first_live) {
-        const int fl = *a.first_live;   // uniform: a scalar load
-        if (a.launch < fl) return;
-        use_in = HAS_IN && a.launch > fl;
-    }
-    if (a.dyn_rows) {
-        const int r = *a.dyn_rows;
-        if (a.dyn_is_k) K = min(K, r); else M = min(M, r);
-    }
-    if (a.dyn_ksplit) ksplit = min(ksplit, max(1, *a.dyn_ksplit));
-    (void)use_in;
+    const FgResolved rs = fg_resolve(a, HAS_IN);
+    if (rs.skip) return;
+    const int M = rs.M, K = rs.K, ksplit = rs.ksplit;
+    const bool use_in = rs.use_in;
     // The tile sequence covers the live rows only (a dynamic M can be smaller than the M the
     // grid was sized for): the live tiles are dealt evenly to the XCDs, and the workgroups
     // that are left over have the highest ids, are dispatched last and return at once.
@@ -306,18 +518,24 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
     const int tiles = tiles_m * a.tiles_n;
     const int total = tiles * ksplit;
     const int per_xcd = (total + FG_XCDS - 1) / FG_XCDS;
-    const int in_xcd = (int)blockIdx.x / FG_XCDS;
-    const int seq_all = ((int)blockIdx.x % FG_XCDS) * per_xcd + in_xcd;
+    const int xcd = (int)blockIdx.x % FG_XCDS;
+    int in_xcd = (int)blockIdx.x / FG_XCDS;
+    // a tile of the last round that is cut along K: range tail_i of tail_n, partial block tail_blk
+    int tail_i = 0, tail_n = 1, tail_blk = 0;
+    if (a.tail_s > 1 && in_xcd >= a.tail_begin) {
+        const int u = in_xcd - a.tail_begin;
+        if (u >= a.tail_r * a.tail_s) return;
+        const int slot = u % a.tail_r;
+        in_xcd = a.tail_begin + slot;
+        tail_i = u / a.tail_r;
+        tail_n = a.tail_s;
+        tail_blk = (xcd * a.tail_r + slot) * a.tail_s + tail_i;
+    }
+    const int seq_all = xcd * per_xcd + in_xcd;
     if (in_xcd >= per_xcd || seq_all >= total) return;
     const int split = seq_all / tiles;
-    const int seq = seq_all - split * tiles;
-    const int group_size = FG_GROUP_M * a.tiles_n;
-    const int grp = seq / group_size;
-    const int first_m = grp * FG_GROUP_M;
-    const int gm = min(FG_GROUP_M, tiles_m - first_m);
-    const int rem = seq - grp * group_size;
-    const int pm = first_m + rem % gm, pn = rem / gm;
-    const int m0 = pm * FG_BM, n0 = pn * FG_BN;
+    int m0, n0;
+    fg_tile_origin(seq_all - split * tiles, tiles_m, a.tiles_n, m0, n0);
 
     FgOperand<A_KM> opa;
     FgOperand<B_KM> opb;
@@ -423,8 +641,10 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
 
     // K steps [k_begin, k_begin + nk) belong to this workgroup
     const int steps_all = (K + FG_BK - 1) / FG_BK;
-    const int k_begin = (int)((int64_t)steps_all * split / ksplit);
-    const int nk = (int)((int64_t)steps_all * (split + 1) / ksplit) - k_begin;
+    // (a launch cut into K ranges as a whole, ksplit > 1, has no tail ranges: tail_n = 1)
+    const int kr_i = tail_n > 1 ? tail_i : split, kr_n = tail_n > 1 ? tail_n : ksplit;
+    const int k_begin = (int)((int64_t)steps_all * kr_i / kr_n);
+    const int nk = (int)((int64_t)steps_all * (kr_i + 1) / kr_n) - k_begin;
     opa.start_at(k_begin);
     opb.start_at(k_begin);
     opa.load(smem, 0, 0, uwave);
@@ -448,64 +668,21 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
     if (t < nk) step(std::integral_constant<int, 1>{}, t++);
     if (t < nk) step(std::integral_constant<int, 2>{}, t++);
     if (t < nk) step(std::integral_constant<int, 3>{}, t++);
-    constexpr int ES = (int)sizeof(OutT);
-    constexpr int EW = 16 / ES;                 // output elements per lane and access: 4 or 8
-    constexpr int LANES_PER_ROW = 128 / EW;     // 32 or 16
-    constexpr int ROWS_PER_ACCESS = 64 / LANES_PER_ROW;   // rows one wavefront-wide access covers: 2 or 4
-    constexpr int PITCH = 128 + 4;              // fp32 words per staged row: 16 lanes' 16-byte writes of one column group hit 64 different banks
-    const int frow = lane & 31, fhalf = lane >> 5;
-    const int rows_c = min(FG_BM, M - m0);
-    const int ldc = (int)a.ldc, ldcin = (int)a.ldcin;
-    const __amdgpu_buffer_rsrc_t rsrc_c =
-        fg_make_rsrc(static_cast<OutT*>(a.C) + (int64_t)split * a.split_stride + (int64_t)m0 * a.ldc,
-                     (uint32_t)rows_c * (uint32_t)ldc * (uint32_t)ES);
-    __amdgpu_buffer_rsrc_t rsrc_in = rsrc_c;
-    if constexpr (HAS_IN)   // a range of zero bytes makes every addend load return zero without touching memory
-        rsrc_in = fg_make_rsrc(static_cast<const unsigned char*>(a.Cin) + (int64_t)m0 * a.ldcin * IS,
-                               use_in ? (uint32_t)rows_c * (uint32_t)ldcin * (uint32_t)IS : 0u);
+    // Where the tile goes: to C (plus addend), or, for a K range of a tail tile, to its fp32
+    // partial block (256 x 256, dense).  The first addend slice is requested before the last
+    // MFMAs.
     const int uwm = __builtin_amdgcn_readfirstlane(wm), uwn = __builtin_amdgcn_readfirstlane(wn);
-    float* stage = reinterpret_cast<float*>(smem + uwave * (FG_LDS_BYTES / 4));   // 40 KB per wavefront
-    // output mapping of the lane: row (inside a group of ROWS_PER_ACCESS) and first column
-    const int orow = lane / LANES_PER_ROW, ocol = (lane % LANES_PER_ROW) * EW;
-    const int colw = n0 + uwn * 128;                       // first column of the wavefront's sub-tile
-    // columns are written in groups of EW; C rows must be allocated up to N rounded up to EW
-    const bool col_ok = colw + ocol < ((a.N + EW - 1) / EW) * EW;
-    const int lane_off = (orow * ldc + ocol) * ES;
-    const int lane_off_in = (orow * ldcin + ocol) * IS;
-    constexpr int NACC = 32 / ROWS_PER_ACCESS;             // accesses per 32-row pass: 16 or 8
-    constexpr int INW = HAS_IN ? EW * IS / 4 : 1;          // dwords of addend per lane and access
-    // Addend of pass `pass` (rows 32 pass .. + 31 of the wavefront's sub-tile) into buffer B.
-    // Two buffers: a pass's addend is requested one pass ahead, the first one before the last
-    // MFMAs of the K loop, so that the memory latency (a few thousand cycles: the addend comes
-    // from HBM) is not waited for in every pass.
-    uint32_t old2[HAS_IN ? 2 : 1][NACC][INW];
-    auto load_addend = [&](auto buf_, int pass) {
-        constexpr int B = decltype(buf_)::value;
-        const int row0 = uwm * 128 + pass * 32;
-#pragma unroll
-        for (int k = 0; k < NACC; ++k) {
-            const int soff = ((row0 + k * ROWS_PER_ACCESS) * ldcin + colw) * IS;
-            if constexpr (INW == 4) {
-                const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc_in, lane_off_in, soff, 0);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) old2[B][k][e] = v[e];
-            } else if constexpr (INW == 8) {
-                const u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(rsrc_in, lane_off_in, soff, 0);
-                const u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(rsrc_in, lane_off_in + 16, soff, 0);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    old2[B][k][e] = v0[e];
-                    old2[B][k][4 + e] = v1[e];
-                }
-            } else {   // 8 bf16 = 4 dwords, or 4 bf16 = 2 dwords
-                static_assert(INW == 2, "addend width");
-                const auto v = __builtin_amdgcn_raw_buffer_load_b64(rsrc_in, lane_off_in, soff, 0);
-                old2[B][k][0] = v[0];
-                old2[B][k][1] = v[1];
-            }
-        }
-    };
-    if constexpr (HAS_IN) load_addend(std::integral_constant<int, 0>{}, 0);
+    FgOut<OutT, InT> out;
+    FgOut<float, void> part;
+    if (tail_n > 1) {
+        part.init(a.tail_part + (size_t)tail_blk * FG_TAIL_BLOCK_FLOATS, FG_BN, nullptr, 0, false, FG_BM, 0, FG_BN,
+                  smem, lane, uwave, uwm, uwn);
+    } else {
+        out.init(static_cast<OutT*>(a.C) + (int64_t)split * a.split_stride + (int64_t)m0 * a.ldc, (int)a.ldc,
+                 HAS_IN ? static_cast<const unsigned char*>(a.Cin) + (int64_t)m0 * a.ldcin * IS : nullptr,
+                 (int)a.ldcin, use_in, min(FG_BM, M - m0), n0, a.N, smem, lane, uwave, uwm, uwn);
+        out.template load_addend<0>(0);
+    }
     {   // sub-step 3 of the last tile
         fg_wait(raw_a[1], raw_b[1]);
 #pragma unroll
@@ -520,82 +697,52 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
     // retire and its LDS be handed to another one).
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
 
-    // ---- epilogue.  The MFMAs are fed the B fragment first and the A fragment second, so
-    // accumulator register g of lane l is ROW l%32, column 8*(g/4)+4*(l/32)+g%4 of its
-    // 32 x 32 tile: four consecutive columns per group of four registers.  Written straight
-    // from the registers, a store instruction would touch 32 different rows.  The memory pipe's cost is per
-    // instruction (about 9 cycles of the CU's address unit per wavefront-wide store,
-    // whatever it carries: measured), so the tile goes through LDS instead, which is
-    // free now: each wavefront stages 32 rows x 128 columns of its 128 x 128 sub-tile
-    // as fp32 in its own LDS region, reads them back row-major, 16 bytes of output per
-    // lane (4 fp32 or 8 bf16 consecutive columns), adds the addend (loaded with the
-    // same wide, row-contiguous accesses) and stores 16 bytes per lane: 16 or 8 times
-    // fewer memory instructions, each writing whole row segments.  Loads and stores go
-    // through buffer descriptors that cover the tile's valid rows (rows past M are
-    // dropped by the range check). ----
+    // ---- epilogue (see FgOut) ----
+    if (tail_n > 1) part.write(acc); else out.write(acc);
+}
+
+// Second step of a launch whose last round was cut along K: adds the tail_s fp32 partial
+// blocks of every tail tile in the fixed order 0, 1, ..., adds the addend, and writes the
+// tile to C.  Same arguments as the product launch; grid = FG_XCDS * tail_r tiles x 8
+// slabs of 32 rows, 256 threads: a thread owns 4 consecutive columns of 4 rows of its slab.
+template <typename OutT, typename InT>
+__global__ __launch_bounds__(256) void fg_tail_reduce_kernel(FGArgs a) {
+    constexpr bool HAS_IN = !std::is_void<InT>::value;
+    const FgResolved rs = fg_resolve(a, HAS_IN);
+    if (rs.skip || a.tail_s <= 1) return;
+    const int tiles_m = (rs.M + FG_BM - 1) / FG_BM;
+    const int tiles = tiles_m * a.tiles_n;            // launches with tail ranges have ksplit = 1
+    const int per_xcd = (tiles + FG_XCDS - 1) / FG_XCDS;
+    const int tile_id = (int)blockIdx.x / 8, slab = (int)blockIdx.x % 8;
+    const int xcd = tile_id / a.tail_r, slot = tile_id % a.tail_r;
+    const int in_xcd = a.tail_begin + slot;
+    const int seq = xcd * per_xcd + in_xcd;
+    if (in_xcd >= per_xcd || seq >= tiles) return;
+    int m0, n0;
+    fg_tile_origin(seq, tiles_m, a.tiles_n, m0, n0);
+    const float* blk = a.tail_part + (size_t)((xcd * a.tail_r + slot) * a.tail_s) * FG_TAIL_BLOCK_FLOATS;
+    const int c4 = ((int)threadIdx.x % 64) * 4;       // first of the thread's 4 columns inside the tile
+    const int col = n0 + c4;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {                          // pass: rows 32 i .. 32 i + 31 of the sub-tile
-        const int row0 = uwm * 128 + i * 32;
-        // the next pass's addend is requested before this pass is staged: it arrives while this
-        // pass goes through LDS
+    for (int p = 0; p < 8; ++p) {
+        const int r = slab * 32 + p * 4 + (int)threadIdx.x / 64;   // row inside the tile
+        const int row = m0 + r;
+        if (row >= rs.M || col >= a.N) continue;
+        f32x4 v = *reinterpret_cast<const f32x4*>(blk + (size_t)r * FG_BN + c4);
+        for (int t = 1; t < a.tail_s; ++t)
+            v += *reinterpret_cast<const f32x4*>(blk + (size_t)t * FG_TAIL_BLOCK_FLOATS + (size_t)r * FG_BN + c4);
+        OutT* dst = static_cast<OutT*>(a.C) + (int64_t)row * a.ldc + col;
         if constexpr (HAS_IN) {
-            if (i == 0) load_addend(std::integral_constant<int, 1>{}, 1);
-            if (i == 1) load_addend(std::integral_constant<int, 0>{}, 2);
-            if (i == 2) load_addend(std::integral_constant<int, 1>{}, 3);
+            if (rs.use_in) {
+                const InT* src = static_cast<const InT*>(a.Cin) + (int64_t)row * a.ldcin + col;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (col + e < a.N) v[e] += to_f32(src[e]);
+            }
         }
-        uint32_t (&old)[NACC][INW] = old2[HAS_IN ? (i & 1) : 0];
-        // stage the pass: the lane holds row frow and, per group of four registers, the four
-        // consecutive columns 32 j + 8 (g/4) + 4 fhalf .. + 3 (the MFMAs are fed B first, A
-        // second, so the accumulators hold the transposed 32 x 32 tiles): one 16-byte LDS
-        // write per group
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                // read the elements into scalars first: a bit_cast applied directly
-                // to an accumulator vector element is miscompiled by this toolchain
-                const float v0 = acc[i][j][4 * g4], v1 = acc[i][j][4 * g4 + 1], v2 = acc[i][j][4 * g4 + 2],
-                            v3 = acc[i][j][4 * g4 + 3];
-                const f32x4 q = {v0, v1, v2, v3};
-                *reinterpret_cast<f32x4*>(stage + frow * PITCH + 32 * j + 8 * g4 + 4 * fhalf) = q;
-            }
-        // The region is private to the wavefront and LDS executes a wavefront's accesses in
-        // order: no workgroup barrier is needed, only that the compiler keeps the order (a
-        // barrier of the usual kind would also wait for the global stores of the previous
-        // pass to be acknowledged: measured 1 000 cycles per pass).
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-        for (int k = 0; k < NACC; ++k) {
-            const float* src = stage + (k * ROWS_PER_ACCESS + orow) * PITCH + ocol;
-            float v[EW];
-#pragma unroll
-            for (int e = 0; e < EW; e += 4) {
-                const f32x4 q = *reinterpret_cast<const f32x4*>(src + e);
-#pragma unroll
-                for (int u = 0; u < 4; ++u) v[e + u] = q[u];
-            }
-            if constexpr (HAS_IN) {
-#pragma unroll
-                for (int e = 0; e < EW; ++e) {
-                    if constexpr (IS == 4) v[e] += __uint_as_float(old[k][e]);
-                    else v[e] += __uint_as_float((e & 1) ? (old[k][e >> 1] & 0xffff0000u) : (old[k][e >> 1] << 16));
-                }
-            }
-            const int soff = ((row0 + k * ROWS_PER_ACCESS) * ldc + colw) * ES;
-            u32x4 out;
-            if constexpr (ES == 4) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) out[e] = __float_as_uint(v[e]);
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const bf16x2 p2 = {from_f32<bf16_t>(v[2 * e]), from_f32<bf16_t>(v[2 * e + 1])};
-                    out[e] = __builtin_bit_cast(uint32_t, p2);
-                }
-            }
-            if (col_ok) __builtin_amdgcn_raw_buffer_store_b128(out, rsrc_c, lane_off, soff, 0);
-        }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the next pass rewrites the region
+        for (int e = 0; e < 4; ++e)
+            if (col + e < a.N) dst[e] = from_f32<OutT>(v[e]);
     }
 }
 

@@ -21,6 +21,7 @@
 namespace flce {
 
 constexpr int64_t CHUNK_ALIGN = 256;   // chunk rows are a multiple of the GEMM macro tile
+constexpr size_t TAIL_PARTIAL_BYTES = (size_t)8 * 32 * 256 * 256 * sizeof(float);   // 64 MiB
 
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 inline size_t elem_size(int dtype) { return dtype == 0 ? 4 : 2; }
@@ -41,7 +42,7 @@ struct Plan {
     // byte offsets into the workspace
     size_t off_hdr = 0, off_row_loss = 0, off_z = 0, off_gt = 0, off_wt = 0, off_xt = 0,
            off_dwacc = 0, off_dxpart = 0, off_xg = 0, off_dxg = 0, off_idx = 0, off_tv = 0,
-           off_dyn = 0, total = 0;
+           off_dyn = 0, off_tail = 0, total = 0;
 };
 
 // How many K ranges to cut a product with `tiles` output tiles and `ksteps` K steps
@@ -145,6 +146,9 @@ inline void lay_out(Plan& p, int64_t H, int64_t V, int dtype, int64_t rows_last,
     p.off_idx = take(p.compact ? (size_t)p.C * sizeof(int32_t) : 0);
     p.off_tv = take(p.compact ? (size_t)p.C * sizeof(int64_t) : 0);
     p.off_dyn = take(256);
+    // fp32 partial blocks of the dW product's last, partly filled round of tiles when it is cut
+    // along K (at most 32 blocks of 256 x 256 per XCD)
+    p.off_tail = take((p.fast_dw_full && p.fast_dw_last) ? TAIL_PARTIAL_BYTES : 0);
     p.total = off;
 }
 

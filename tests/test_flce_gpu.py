@@ -436,3 +436,22 @@ def test_options_passed_with_the_call_equal_the_setters():
     loss_k, dX_k, dW_k = flce.flce_fwd_bwd_opt(X, W, t, skip, w.ignore_index)
     torch.cuda.synchronize()
     assert dX_k is None and abs(loss_k.item() - ref.loss) <= TOL["bf16"][0] * abs(ref.loss)
+
+
+@pytest.mark.parametrize("chunks", [1, 2])
+def test_dw_last_round_of_tiles_is_cut_along_k(chunks):
+    # dW has 65 x 4 = 260 output tiles: 33 per XCD, i.e. one more than a round of 32 CUs, so the
+    # last tile of every XCD's span is cut into K ranges (fp32 partial blocks, fixed-order sum by
+    # a second launch).  One chunk: the sum is written as bf16; two chunks: fp32 partial sums of
+    # dW across the chunks, the tail tiles of both launches go through the same reduction
+    import paper_2410_10989_amd as flce
+    w = workloads.make(4096, 1024, 16640, "bf16", targets="zipf", ignore=("iid", 0.1), seed=260 + chunks,
+                       name="dw_tail")
+    old = flce.flce_get_logits_budget_bytes()
+    try:
+        if chunks == 2:
+            flce.flce_set_logits_budget_bytes(2048 * 16640 * 2)
+        assert flce.flce_num_chunks(w.BT, w.H, w.V, flce.FLCE_BF16) == chunks
+        check_full(w)
+    finally:
+        flce.flce_set_logits_budget_bytes(old)
