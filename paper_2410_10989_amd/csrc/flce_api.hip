@@ -201,15 +201,15 @@ struct FastDyn {
 };
 
 // Tuned bf16 kernel (see gemm_bf16_nt.h for what A_KM / B_KM / InT mean).  The
-// caller has checked the shape limits (Plan::fast_*).  tail_part: room for
-// FG_TAIL_MAX_BLOCKS partial blocks; when given (and the launch is not cut into K ranges
-// as a whole and its tile count is known here), the tiles of a poorly filled last round
-// are cut along K and summed by a second, small launch.
+// caller has checked the shape limits (Plan::fast_*).  tail_part: tail_bytes of
+// room for fp32 partial blocks; when that is enough for the launch's tail_plan (and the
+// launch is not cut into K ranges as a whole and its tile count is known here), the tiles
+// of a poorly filled last round are cut along K and summed by a second, small launch.
 template <typename OutT, typename InT, bool A_KM, bool B_KM>
 int launch_gemm_fast(int kind, const bf16_t* A, int64_t lda, const bf16_t* B, int64_t ldb, OutT* C,
                      int64_t ldc, const InT* Cin, int64_t ldcin, int64_t M, int64_t N, int64_t K,
                      hipStream_t s, int ksplit = 1, int64_t split_stride = 0, const FastDyn& d = FastDyn{},
-                     float* tail_part = nullptr) {
+                     float* tail_part = nullptr, size_t tail_bytes = 0) {
     if (M <= 0 || N <= 0 || K <= 0) return FLCE_OK;
     if (!aligned(A, 16) || !aligned(B, 16)) return FLCE_ERR_ARG;
     ScopedKernelTimer timer(kind, s);
@@ -221,8 +221,8 @@ int launch_gemm_fast(int kind, const bf16_t* A, int64_t lda, const bf16_t* B, in
     int64_t wgs_per_xcd = (total + FG_XCDS - 1) / FG_XCDS;
     const bool m_static = !(d.rows && !d.is_k);   // a dynamic M changes the tile count on the device
     if (tail_part && ksplit == 1 && !d.ksplit && m_static) {
-        const FgTailPlan t = fg_tail_plan(total, (K + FG_BK - 1) / FG_BK);
-        if (t.s > 1) {
+        const TailPlan t = tail_plan(total, (K + FG_BK - 1) / FG_BK);
+        if (t.s > 1 && (size_t)FG_XCDS * t.r * t.s * TAIL_BLOCK_BYTES <= tail_bytes) {
             a.tail_begin = t.begin;
             a.tail_r = t.r;
             a.tail_s = t.s;
@@ -364,7 +364,6 @@ int run_head(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t
     int64_t* tv = reinterpret_cast<int64_t*>(ws + p.off_tv);
     int* dyn = reinterpret_cast<int*>(ws + p.off_dyn);   // [0] row cursor, [1] live rows of the chunk
     float* tail = reinterpret_cast<float*>(ws + p.off_tail);   // partial blocks of the dW product's last round
-    static_assert(TAIL_PARTIAL_BYTES == FG_TAIL_MAX_BLOCKS * FG_TAIL_BLOCK_FLOATS * sizeof(float), "tail blocks");
     constexpr int VEC = 16 / (int)sizeof(T);
 
     hipLaunchKernelGGL(count_valid_kernel, dim3(1), dim3(1024), 0, s, targets, BT, ignore_index,
@@ -518,19 +517,19 @@ int run_head(const T* X, const T* W, const int64_t* targets, int64_t BT, int64_t
                     if (p.nchunks == 1) {
                         FLCE_TRY((launch_gemm_fast<bf16_t, void, true, true>(
                             FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dW, H, nullptr, 0, V, H, rows, s, 1, 0,
-                            dyn_dw, tail)));
+                            dyn_dw, tail, p.tail_bytes)));
                     } else if (c == 0) {
                         FLCE_TRY((launch_gemm_fast<float, void, true, true>(
                             FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dWacc, H, nullptr, 0, V, H, rows, s, 1, 0,
-                            dyn_dw, tail)));
+                            dyn_dw, tail, p.tail_bytes)));
                     } else if (!last) {
                         FLCE_TRY((launch_gemm_fast<float, float, true, true>(
                             FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dWacc, H, dWacc, H, V, H, rows, s, 1, 0,
-                            dyn_dw, tail)));
+                            dyn_dw, tail, p.tail_bytes)));
                     } else {   // last chunk: add the fp32 partial sums and write dW in bf16
                         FLCE_TRY((launch_gemm_fast<bf16_t, float, true, true>(
                             FLCE_KIND_DW_GEMM, Z, p.ldz, Xc, H, dW, H, dWacc, H, V, H, rows, s, 1, 0,
-                            dyn_dw, tail)));
+                            dyn_dw, tail, p.tail_bytes)));
                     }
                 }
             } else {

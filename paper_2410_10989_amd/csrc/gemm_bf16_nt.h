@@ -64,6 +64,7 @@
 #include <type_traits>
 
 #include "flce_device.h"
+#include "scheduler.h"
 
 namespace flce {
 
@@ -101,7 +102,7 @@ struct FGArgs {
     // taken as zero (not read) unless launch > *first_live.
     const int* first_live;
     int launch;
-    // Tiles of the last, partly filled round cut along K (see fg_tail_plan): from position
+    // Tiles of the last, partly filled round cut along K (see tail_plan): from position
     // tail_begin of an XCD's tile span on, the next tail_r tiles are computed as tail_s K
     // ranges each by tail_r * tail_s workgroups, which write fp32 partial blocks of 256 x
     // 256 to tail_part; fg_tail_reduce_kernel adds them up and writes C.  tail_s <= 1: off.
@@ -109,32 +110,8 @@ struct FGArgs {
     float* tail_part;
 };
 
-// A launch of one workgroup per tile runs in rounds of as many tiles as the chip has CUs
-// (one tile per CU at a time: a tile takes the whole LDS).  When the last round holds only
-// r <= 16 tiles per XCD, two thirds or more of the CUs would idle through it, so each of
-// those tiles is cut into s = 32 / r K ranges instead (at most 8, each at least 16 K steps
-// long): the round takes 1 / s of a tile's time plus a small reduction.  Returns s (1 = the
-// launch is left as it is); `total` = tiles of the launch, ksteps = K steps per tile.
-struct FgTailPlan {
-    int begin, r, s;
-};
-inline FgTailPlan fg_tail_plan(int64_t total, int64_t ksteps) {
-    constexpr int CUS_PER_XCD = 32;
-    FgTailPlan t{0, 0, 1};
-    const int64_t per_xcd = (total + FG_XCDS - 1) / FG_XCDS;
-    const int r = (int)(per_xcd % CUS_PER_XCD);
-    if (per_xcd < CUS_PER_XCD || r == 0 || r > CUS_PER_XCD / 2) return t;
-    int s = CUS_PER_XCD / r;
-    if (s > 8) s = 8;
-    while (s > 1 && ksteps / s < 16) --s;
-    if (s <= 1) return t;
-    t.begin = (int)(per_xcd - r);
-    t.r = r;
-    t.s = s;
-    return t;
-}
-constexpr int FG_TAIL_MAX_BLOCKS = FG_XCDS * 32;   // partial blocks a launch can need (r * s <= 32 per XCD)
-constexpr size_t FG_TAIL_BLOCK_FLOATS = (size_t)FG_BM * FG_BN;
+constexpr size_t FG_TAIL_BLOCK_FLOATS = (size_t)FG_BM * FG_BN;   // one fp32 partial block of a tail tile
+static_assert(FG_TAIL_BLOCK_FLOATS * sizeof(float) == TAIL_BLOCK_BYTES && FG_XCDS == TAIL_XCDS, "planner and kernel agree on the tail blocks");
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));

@@ -21,7 +21,39 @@
 namespace flce {
 
 constexpr int64_t CHUNK_ALIGN = 256;   // chunk rows are a multiple of the GEMM macro tile
-constexpr size_t TAIL_PARTIAL_BYTES = (size_t)8 * 32 * 256 * 256 * sizeof(float);   // 64 MiB
+
+// A launch of one workgroup per 256 x 256 tile runs in rounds of as many tiles as the chip
+// has CUs (one tile per CU at a time: a tile takes the whole LDS), dealt to the 8 XCDs in
+// equal spans.  When the last round holds only r <= 16 tiles per XCD, half or more of the
+// CUs would idle through it, so each of those tiles is cut into s = 32 / r K ranges instead
+// (at most 8, each at least 16 K steps long): the round takes 1 / s of a tile's time plus a
+// small reduction of fp32 partial blocks.  s = 1: the launch is left as it is.  `total` =
+// tiles of the launch, ksteps = K steps (of 64) per tile; begin = position inside an XCD's
+// span of its first tail tile.
+constexpr int TAIL_XCDS = 8, TAIL_CUS_PER_XCD = 32;
+constexpr size_t TAIL_BLOCK_BYTES = (size_t)256 * 256 * sizeof(float);
+struct TailPlan {
+    int begin, r, s;
+};
+inline TailPlan tail_plan(int64_t total, int64_t ksteps) {
+    TailPlan t{0, 0, 1};
+    const int64_t per_xcd = (total + TAIL_XCDS - 1) / TAIL_XCDS;
+    const int r = (int)(per_xcd % TAIL_CUS_PER_XCD);
+    if (per_xcd < TAIL_CUS_PER_XCD || r == 0 || r > TAIL_CUS_PER_XCD / 2) return t;
+    int s = TAIL_CUS_PER_XCD / r;
+    if (s > 8) s = 8;
+    while (s > 1 && ksteps / s < 16) --s;
+    if (s <= 1) return t;
+    t.begin = (int)(per_xcd - r);
+    t.r = r;
+    t.s = s;
+    return t;
+}
+// bytes of partial blocks such a launch needs (0 when it is not cut)
+inline size_t tail_partial_bytes(int64_t total, int64_t ksteps) {
+    const TailPlan t = tail_plan(total, ksteps);
+    return t.s > 1 ? (size_t)TAIL_XCDS * t.r * t.s * TAIL_BLOCK_BYTES : 0;
+}
 
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 inline size_t elem_size(int dtype) { return dtype == 0 ? 4 : 2; }
@@ -43,6 +75,7 @@ struct Plan {
     size_t off_hdr = 0, off_row_loss = 0, off_z = 0, off_gt = 0, off_wt = 0, off_xt = 0,
            off_dwacc = 0, off_dxpart = 0, off_xg = 0, off_dxg = 0, off_idx = 0, off_tv = 0,
            off_dyn = 0, off_tail = 0, total = 0;
+    size_t tail_bytes = 0;   // room at off_tail
 };
 
 // How many K ranges to cut a product with `tiles` output tiles and `ksteps` K steps
@@ -147,8 +180,10 @@ inline void lay_out(Plan& p, int64_t H, int64_t V, int dtype, int64_t rows_last,
     p.off_tv = take(p.compact ? (size_t)p.C * sizeof(int64_t) : 0);
     p.off_dyn = take(256);
     // fp32 partial blocks of the dW product's last, partly filled round of tiles when it is cut
-    // along K (at most 32 blocks of 256 x 256 per XCD)
-    p.off_tail = take((p.fast_dw_full && p.fast_dw_last) ? TAIL_PARTIAL_BYTES : 0);
+    // along K (tail_plan; a shorter last chunk has fewer K steps and never needs more)
+    const int64_t dw_tiles = ((V + 255) / 256) * ((H + 255) / 256);
+    p.tail_bytes = (p.fast_dw_full && p.fast_dw_last) ? tail_partial_bytes(dw_tiles, (p.C + 63) / 64) : 0;
+    p.off_tail = take(p.tail_bytes);
     p.total = off;
 }
 
