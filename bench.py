@@ -15,7 +15,7 @@ already resident in HBM.  Prints ONE JSON line:
                          takes the most time per step
   dense                  the same workload with row compaction off (every row projected,
                          as the paper does)
-  per_config             all five benchmark workloads, a few passes each
+  per_config             all five benchmark workloads, about 0.3 s of passes each
   memory                 workspace against the full logits for growing BT
   mfma_only_loop         the MFMA instruction alone on register operands, with power
   cpu_baseline           the CPU oracle on a bounded sample of the same workload
@@ -204,8 +204,8 @@ def config_line(flce, w, code, ms, compaction, nh=1, flop_factor=6.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, help="workload 1-5 (3 = Llama-3-8B lm_head)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=1024)
@@ -418,13 +418,14 @@ def main():
     if compaction and not args.no_dense_leg:
         flce.flce_set_row_compaction(False)
         try:
-            dms, _, _ = time_steps(step, 2, bsteps)
+            dsteps = max(bsteps, min(args.steps, 15))
+            dms, _, _ = time_steps(step, 2, dsteps)
         finally:
             flce.flce_set_row_compaction(True)
         dn = flops_step / (dms * 1e-3) / 1e12
         out["dense"] = {"what": "row compaction off: all BT rows projected", "ms_per_step": dms,
                         "tokens_per_s": w.BT / (dms * 1e-3), "tflops_executed": dn,
-                        "mfma_util_frac_of_peak": dn / peak, "steps": bsteps}
+                        "mfma_util_frac_of_peak": dn / peak, "steps": dsteps}
 
     if w.dtype == "bf16" and not args.no_mfma_loop:
         # What the matrix pipes sustain with nothing to feed them from memory: the same MFMA
@@ -477,8 +478,10 @@ def main():
             def step_i():
                 flce.flce_fwd_bwd(Xi, Wi, ti, wi.ignore_index, loss=loss, dX=dXi, dW=dWi)
 
-            n = 20 if idx == 1 else bsteps
-            msi, _, _ = time_steps(step_i, 2, n)
+            # long enough (about 0.3 s) for the clock to settle after the idle time of the upload
+            est, _, _ = time_steps(step_i, 1, 2)
+            n = int(min(200, max(bsteps, -(-300.0 // max(est, 1e-3)))))
+            msi, _, _ = time_steps(step_i, max(2, n // 4), n)
             comp_i = flce.flce_get_row_compaction() and wi.dtype == "bf16" and wi.H % 64 == 0
             line = config_line(flce, wi, ci, msi, comp_i)
             line.update(workload=wi.name, dtype=wi.dtype, steps=n, loss=float(loss.item()),
