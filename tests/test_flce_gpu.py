@@ -438,20 +438,42 @@ def test_options_passed_with_the_call_equal_the_setters():
     assert dX_k is None and abs(loss_k.item() - ref.loss) <= TOL["bf16"][0] * abs(ref.loss)
 
 
-@pytest.mark.parametrize("chunks", [1, 2])
+@pytest.mark.parametrize("chunks", [1, 2, 3])
 def test_dw_last_round_of_tiles_is_cut_along_k(chunks):
     # dW has 65 x 4 = 260 output tiles: 33 per XCD, i.e. one more than a round of 32 CUs, so the
     # last tile of every XCD's span is cut into K ranges (fp32 partial blocks, fixed-order sum by
     # a second launch).  One chunk: the sum is written as bf16; two chunks: fp32 partial sums of
-    # dW across the chunks, the tail tiles of both launches go through the same reduction
+    # dW across the chunks, the tail tiles of both launches go through the same reduction; three:
+    # the middle launch adds fp32 to fp32
     import paper_2410_10989_amd as flce
-    w = workloads.make(4096, 1024, 16640, "bf16", targets="zipf", ignore=("iid", 0.1), seed=260 + chunks,
-                       name="dw_tail")
+    w = workloads.make(2048 * max(chunks, 2), 1024, 16640, "bf16", targets="zipf", ignore=("iid", 0.1),
+                       seed=260 + chunks, name="dw_tail")
     old = flce.flce_get_logits_budget_bytes()
     try:
-        if chunks == 2:
+        if chunks >= 2:
             flce.flce_set_logits_budget_bytes(2048 * 16640 * 2)
+        # (the rows that have a target are dealt evenly to the chunks, 10 % fewer than 2048 each)
         assert flce.flce_num_chunks(w.BT, w.H, w.V, flce.FLCE_BF16) == chunks
         check_full(w)
     finally:
         flce.flce_set_logits_budget_bytes(old)
+
+
+@pytest.mark.parametrize("compaction", [True, False])
+def test_dw_cut_last_round_with_empty_and_ragged_chunks(compaction):
+    # the same dW shape in 3 chunks of 2048 rows at most.  Row compaction on: 70 % of the targets
+    # are ignored, so the first launch has no live rows and returns at once, together with its
+    # second, summing launch; the live launches see fewer K steps than the plan assumed.  Off: the
+    # last chunk has 1904 rows, too few K steps for two ranges: that launch is not cut, the others are
+    import paper_2410_10989_amd as flce
+    w = workloads.make(6000, 1024, 16640, "bf16", targets="zipf", ignore=("iid", 0.7 if compaction else 0.1),
+                       seed=271 + int(compaction), name="dw_tail_ragged")
+    old, old_c = flce.flce_get_logits_budget_bytes(), flce.flce_get_row_compaction()
+    try:
+        flce.flce_set_logits_budget_bytes(2048 * 16640 * 2)
+        flce.flce_set_row_compaction(compaction)
+        assert flce.flce_num_chunks(w.BT, w.H, w.V, flce.FLCE_BF16) == 3
+        check_full(w)
+    finally:
+        flce.flce_set_logits_budget_bytes(old)
+        flce.flce_set_row_compaction(old_c)
