@@ -484,6 +484,13 @@ def main():
             msi, _, _ = time_steps(step_i, max(2, n // 4), n)
             comp_i = flce.flce_get_row_compaction() and wi.dtype == "bf16" and wi.H % 64 == 0
             line = config_line(flce, wi, ci, msi, comp_i)
+            if msi < 1.0:
+                # launch-bound: the same call recorded once into a HIP graph and replayed
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):
+                    step_i()
+                line["graph_replay_ms"], _, _ = time_steps(graph.replay, max(2, n // 4), n)
+                del graph
             line.update(workload=wi.name, dtype=wi.dtype, steps=n, loss=float(loss.item()),
                         mfma_util_frac_of_peak=line["tflops_executed"] / MFMA_PEAK_TFLOPS[wi.dtype])
             per[f"config{idx}"] = line
