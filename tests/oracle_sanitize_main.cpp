@@ -128,6 +128,41 @@ static void oracle_case(int64_t BT, int64_t H, int64_t V, int every_nth_ignored,
     CHECK(worst <= 1e-14, "CE dlogits differ from the fused oracle's by %g", worst);
 }
 
+// The cut of a launch's last round of tiles along K: whatever the tile count and the K length,
+// the cut tiles are the last r <= 16 of every XCD's span, r * s workgroups fit one round of an
+// XCD's 32 CUs, every range keeps at least 16 K steps, the ranges partition the K steps, and a
+// shorter K never needs more room than a longer one (the plan sizes the room for full chunks).
+static void tail_plan_sweep() {
+    long cut = 0, all = 0;
+    for (int64_t total = 1; total <= 40000; total += (total < 600 ? 1 : 37))
+        for (int64_t ksteps = 1; ksteps <= 2100; ksteps += (ksteps < 140 ? 1 : 97)) {
+            const flce::TailPlan t = flce::tail_plan(total, ksteps);
+            const int64_t per_xcd = (total + 7) / 8;
+            ++all;
+            CHECK(t.s >= 1 && t.s <= 8, "s out of range");
+            CHECK(flce::tail_partial_bytes(total, ksteps) ==
+                      (t.s > 1 ? (size_t)8 * t.r * t.s * 256 * 256 * 4 : (size_t)0), "bytes of partial blocks");
+            if (ksteps > 1)
+                CHECK(flce::tail_partial_bytes(total, ksteps - 1) <= flce::tail_partial_bytes(total, ksteps),
+                      "a shorter K needs more room (total %lld ksteps %lld)", (long long)total, (long long)ksteps);
+            if (t.s == 1) continue;
+            ++cut;
+            CHECK(t.r >= 1 && t.r <= 16 && t.r * t.s <= 32, "r %d s %d do not fit a round", t.r, t.s);
+            CHECK(t.begin + t.r == per_xcd && t.begin % 32 == 0 && t.begin >= 32, "position of the cut tiles");
+            CHECK(ksteps / t.s >= 16, "a range of fewer than 16 K steps");
+            int64_t covered = 0, prev_end = 0;
+            for (int i = 0; i < t.s; ++i) {
+                const int64_t b = ksteps * i / t.s, e = ksteps * (i + 1) / t.s;
+                CHECK(b == prev_end && e > b, "K ranges do not tile the K steps");
+                covered += e - b;
+                prev_end = e;
+            }
+            CHECK(covered == ksteps, "K steps lost");
+        }
+    std::printf("tail plan: %ld launches checked, %ld of them cut\n", all, cut);
+    CHECK(cut > 0, "no launch was cut");
+}
+
 static void scheduler_sweep() {
     using flce::Plan;
     const int64_t Hs[] = {1, 8, 64, 100, 512, 2304, 3584, 4096, 8192};
@@ -150,13 +185,15 @@ static void scheduler_sweep() {
                             CHECK(p.ldz >= V && p.ldz % 64 == 0 && p.ldc >= p.C, "leading dimensions");
                             const size_t offs[] = {p.off_hdr, p.off_row_loss, p.off_z, p.off_gt, p.off_wt,
                                                    p.off_xt, p.off_dwacc, p.off_dxpart, p.off_xg, p.off_dxg,
-                                                   p.off_idx, p.off_tv, p.off_dyn, p.total};
+                                                   p.off_idx, p.off_tv, p.off_dyn, p.off_tail, p.total};
                             for (size_t k = 0; k + 1 < sizeof(offs) / sizeof(offs[0]); ++k)
                                 CHECK(offs[k] % 256 == 0 && offs[k] <= offs[k + 1], "workspace layout");
                             CHECK(p.off_z - p.off_row_loss >= (size_t)p.C * 4, "row losses overlap the logits");
                             CHECK(p.total <= cap.total, "workspace %zu above the bound %zu (BT %lld H %lld V %lld)",
                                   p.total, cap.total, (long long)BT, (long long)H, (long long)V);
                             CHECK(p.dx_ksplit >= 1 && p.dx_ksplit <= 16, "K ranges");
+                            CHECK(p.total - p.off_tail >= p.tail_bytes && p.tail_bytes <= ((size_t)64 << 20),
+                                  "room for the partial blocks of the dW product's last round");
                         }
                 }
     std::printf("scheduler: %ld plans checked\n", plans);
@@ -171,6 +208,7 @@ int main() {
     oracle_case(70, 8, 11, 1, false);    // no valid row at all
     oracle_case(67, 4, 17, 0, true);     // W = 0: loss = log V
     scheduler_sweep();
+    tail_plan_sweep();
     if (failures) {
         std::printf("%d check(s) failed\n", failures);
         return 1;
