@@ -45,7 +45,7 @@
  *    device on first use and keeps it (growing it if a later call needs more;
  *    growing synchronises the device).  Calls that overlap in time on the same
  *    device share the workspace and therefore race: serialise them on one
- *    stream.
+ *    stream, or give each call a workspace of its own (flce_options).
  *  - Once the workspace is large enough (after a first call of the same size, or
  *    with a lent buffer) a call consists of kernel launches on `stream` only: no
  *    allocation, no memset, no synchronisation.  It can therefore be recorded
@@ -116,15 +116,28 @@ FLCE_API int flce_fwd_bwd_ex(const void* X, const void* W, const int64_t* target
  *   logits_budget_bytes  bytes one chunk of logits may take, 0 = the automatic rule
  *   row_compaction       0 or 1
  *   flags                FLCE_SKIP_*
- * flce_default_options fills a struct with the current process-wide settings and
- * flags = 0.  opt == NULL means exactly that.  flce_workspace_bytes_opt is
- * flce_workspace_bytes for such a call (0 for bad arguments).
+ *   workspace            device buffer (256-byte aligned) that THIS call uses as its
+ *                        scratch memory instead of the device's shared workspace, or
+ *                        NULL for the shared one; owned by the caller, who keeps it
+ *                        alive until the call's work on the stream has finished
+ *   workspace_bytes      its size: at least flce_workspace_bytes_opt of the same
+ *                        arguments (FLCE_ERR_WORKSPACE otherwise; FLCE_ERR_ALIGN for
+ *                        a misaligned buffer)
+ * Calls that bring their own workspace share nothing on the device, so they may
+ * overlap on one GPU (different streams, different threads) as long as their
+ * workspaces and outputs are distinct.
+ * flce_default_options fills a struct with the current process-wide settings,
+ * flags = 0 and no workspace.  opt == NULL means exactly that.
+ * flce_workspace_bytes_opt is flce_workspace_bytes for such a call (0 for bad
+ * arguments).
  */
 typedef struct {
     size_t size;
     size_t logits_budget_bytes;
     int row_compaction;
     unsigned flags;
+    void* workspace;
+    size_t workspace_bytes;
 } flce_options;
 FLCE_API void flce_default_options(flce_options* opt);
 FLCE_API int flce_fwd_bwd_opt(const void* X, const void* W, const int64_t* targets, int64_t BT, int64_t H,

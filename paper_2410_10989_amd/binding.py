@@ -141,13 +141,20 @@ def flce_fwd_bwd(X, W, targets, ignore_index=-100, loss=None, dX=None, dW=None, 
 class FlceOptions(ctypes.Structure):
     """flce_options of include/flce.h."""
     _fields_ = [("size", ctypes.c_size_t), ("logits_budget_bytes", ctypes.c_size_t),
-                ("row_compaction", ctypes.c_int), ("flags", ctypes.c_uint)]
+                ("row_compaction", ctypes.c_int), ("flags", ctypes.c_uint),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
 
 
-def flce_options(logits_budget_bytes=None, row_compaction=None, flags=0) -> FlceOptions:
-    """The process-wide settings (flce_default_options) with the given fields replaced."""
+def flce_options(logits_budget_bytes=None, row_compaction=None, flags=0, workspace=None) -> FlceOptions:
+    """The process-wide settings (flce_default_options) with the given fields replaced.
+    workspace: a device tensor the call uses as its scratch memory instead of the device's
+    shared workspace (kept alive by the returned struct)."""
     o = FlceOptions()
     lib().flce_default_options(ctypes.byref(o))
+    if workspace is not None:
+        o.workspace = _dev_ptr(workspace, "workspace")
+        o.workspace_bytes = workspace.numel() * workspace.element_size()
+        o._workspace_tensor = workspace
     if logits_budget_bytes is not None:
         o.logits_budget_bytes = int(logits_budget_bytes)
     if row_compaction is not None:

@@ -54,6 +54,8 @@ std::atomic<bool> g_compact{true};
 struct Settings {
     size_t budget;   // 0 = the automatic rule
     bool compact;
+    void* ws = nullptr;   // the call's own workspace (flce_options), null = the device's shared one
+    size_t ws_bytes = 0;
 };
 Settings global_settings() { return {g_budget.load(), g_compact.load()}; }
 
@@ -705,8 +707,13 @@ int multihead_fwd_bwd(const Settings& st, const void* X, const void* const* W, c
 
     const Plan p = plan_for(st, BT, H, V, dtype);
     FLCE_TRY(check_launch_limits(p, H, V));
-    char* ws = nullptr;
-    FLCE_TRY(acquire_workspace(p.total, &ws));
+    char* ws = static_cast<char*>(st.ws);
+    if (ws) {
+        if (!aligned(ws, 256)) return FLCE_ERR_ALIGN;
+        if (st.ws_bytes < p.total) return FLCE_ERR_WORKSPACE;
+    } else {
+        FLCE_TRY(acquire_workspace(p.total, &ws));
+    }
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (dtype == FLCE_F32)
         return run_heads<float>(static_cast<const float*>(X), W, targets, weights, n_heads, BT, H, V,
@@ -736,6 +743,8 @@ void flce_default_options(flce_options* opt) {
     opt->logits_budget_bytes = st.budget;
     opt->row_compaction = st.compact ? 1 : 0;
     opt->flags = 0u;
+    opt->workspace = nullptr;
+    opt->workspace_bytes = 0;
 }
 
 // The settings a call's options stand for; FLCE_ERR_ARG for a struct this library cannot read.
@@ -747,6 +756,8 @@ static int settings_from(const flce_options* opt, Settings* st, unsigned* flags)
     if (opt->row_compaction != 0 && opt->row_compaction != 1) return FLCE_ERR_ARG;
     st->budget = opt->logits_budget_bytes;
     st->compact = opt->row_compaction != 0;
+    st->ws = opt->workspace;
+    st->ws_bytes = opt->workspace ? opt->workspace_bytes : 0;
     *flags = opt->flags;
     return FLCE_OK;
 }

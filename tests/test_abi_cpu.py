@@ -190,3 +190,14 @@ def test_options_passed_with_the_call_plan_like_the_setters():
     bad.row_compaction = 5
     assert L.flce_fwd_bwd_opt(a, a + 256, a + 512, 4, 8, 16, -100, 1, a + 768, a + 1024, a + 1280,
                               ctypes.byref(bad), None) == 7
+    # a workspace of the call's own: refused on the host when misaligned or too small
+    need = flce.flce_workspace_bytes_opt(4, 8, 16, code, flce.flce_options())
+    assert need > 0
+    own = flce.flce_options()
+    assert not own.workspace and own.workspace_bytes == 0
+    own.workspace, own.workspace_bytes = a + 2048 + 8, 1 << 30
+    assert L.flce_fwd_bwd_opt(a, a + 256, a + 512, 4, 8, 16, -100, 1, a + 768, a + 1024, a + 1280,
+                              ctypes.byref(own), None) == 4
+    own.workspace, own.workspace_bytes = a + 2048, need - 1
+    assert L.flce_fwd_bwd_opt(a, a + 256, a + 512, 4, 8, 16, -100, 1, a + 768, a + 1024, a + 1280,
+                              ctypes.byref(own), None) == 5

@@ -438,6 +438,53 @@ def test_options_passed_with_the_call_equal_the_setters():
     assert dX_k is None and abs(loss_k.item() - ref.loss) <= TOL["bf16"][0] * abs(ref.loss)
 
 
+def test_calls_with_workspaces_of_their_own_may_overlap():
+    # two different problems on two streams at the same time, each call with a workspace of its
+    # own (flce_options): the same bits as the two calls one after the other on the shared
+    # workspace.  The buffers start out full of NaN bit patterns: the call relies on nothing in them.
+    import paper_2410_10989_amd as flce
+    ws_a = workloads.make(1500, 256, 3000, "bf16", ignore=("iid", 0.2), seed=41, name="own_ws_a")
+    ws_b = workloads.make(900, 256, 5000, "bf16", targets="zipf", ignore=("pad", 128, 40), seed=42, name="own_ws_b")
+    budget = 512 * 3000 * 2                                    # several chunks each
+    seq, ins = [], []
+    try:
+        flce.flce_set_logits_budget_bytes(budget)
+        for w in (ws_a, ws_b):
+            X, W, t = upload(w)
+            ins.append((X, W, t))
+            seq.append(flce.flce_fwd_bwd(X, W, t, w.ignore_index))
+        torch.cuda.synchronize()
+    finally:
+        flce.flce_set_logits_budget_bytes(0)
+    streams = [torch.cuda.Stream() for _ in range(2)]
+    opts, outs = [], []
+    for w in (ws_a, ws_b):
+        need = flce.flce_workspace_bytes_opt(w.BT, w.H, w.V, flce.FLCE_BF16, flce.flce_options(logits_budget_bytes=budget))
+        buf = torch.full((need // 2 + 128,), -1, dtype=torch.int16, device="cuda")
+        off = (-buf.data_ptr() % 256) // 2
+        opts.append(flce.flce_options(logits_budget_bytes=budget, workspace=buf[off:off + need // 2]))
+    torch.cuda.synchronize()
+    for rep in range(3):                                       # the launches of the two calls interleave
+        outs = []
+        for (X, W, t), w, o, st in zip(ins, (ws_a, ws_b), opts, streams):
+            outs.append(flce.flce_fwd_bwd_opt(X, W, t, o, w.ignore_index, stream=st))
+        torch.cuda.synchronize()
+        for (l1, dx1, dw1), (l2, dx2, dw2) in zip(seq, outs):
+            assert l1.item() == l2.item()
+            assert torch.equal(dx1.view(torch.int16), dx2.view(torch.int16))
+            assert torch.equal(dw1.view(torch.int16), dw2.view(torch.int16))
+    ref = oracle.flce(ws_b.X, ws_b.W, ws_b.targets, ws_b.ignore_index)
+    assert_close("dW", to_host(outs[1][2]), ref.dW, TOL["bf16"][1])
+    assert_close("dX", to_host(outs[1][1]), ref.dX, TOL["bf16"][1])
+    # a buffer one byte short is refused before anything is launched
+    w, (X, W, t) = ws_a, ins[0]
+    need = flce.flce_workspace_bytes_opt(w.BT, w.H, w.V, flce.FLCE_BF16, flce.flce_options(logits_budget_bytes=budget))
+    short = flce.flce_options(logits_budget_bytes=budget, workspace=opts[0]._workspace_tensor[:need // 2 - 1])
+    with pytest.raises(flce.FlceError) as e:
+        flce.flce_fwd_bwd_opt(X, W, t, short, w.ignore_index)
+    assert e.value.status == 5
+
+
 @pytest.mark.parametrize("chunks", [1, 2, 3])
 def test_dw_last_round_of_tiles_is_cut_along_k(chunks):
     # dW has 65 x 4 = 260 output tiles: 33 per XCD, i.e. one more than a round of 32 CUs, so the
