@@ -168,7 +168,8 @@ def test_large_logits_do_not_overflow():
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("BT,V,pad", [(37, 1000, 0), (16, 4099, 5), (3, 7, 0), (200, 40960, 0)])
+@pytest.mark.parametrize("BT,V,pad", [(37, 1000, 0), (16, 4099, 5), (3, 7, 0), (200, 40960, 0),
+                                        (70001, 136, 0)])   # the last: more rows than one launch of the row kernel takes
 def test_standalone_cross_entropy(dtype, BT, V, pad):
     import paper_2410_10989_amd as flce
     g = np.random.default_rng(BT * 7 + V)
@@ -189,6 +190,17 @@ def test_standalone_cross_entropy(dtype, BT, V, pad):
     assert_close("dZ", to_host(view), ref_G, rg)
     if pad:
         assert (to_host(buf[:, V:]) == 0).all()   # the row padding is not touched
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_one_chunk_of_more_than_65536_rows(dtype):
+    # a small vocabulary makes the automatic budget hold the whole batch: ONE chunk of 150 001 rows,
+    # i.e. 586 tile rows in the products, a row kernel launched in three pieces, and (bf16) the
+    # row compaction collecting 105 000 rows in one go
+    import paper_2410_10989_amd as flce
+    w = workloads.make(150001, 64, 200, dtype, ignore=("iid", 0.3), seed=77, name="many_rows")
+    assert flce.flce_num_chunks(w.BT, w.H, w.V, flce.FLCE_BF16 if dtype == "bf16" else flce.FLCE_F32) == 1
+    check_full(w)
 
 
 def test_ragged_vocabulary_with_a_poisoned_workspace():
