@@ -57,6 +57,8 @@ def test_config1_tiny_fp32():
     (640, 1032, 4096, ("iid", 0.1)),    # guarded kernels over many tiles and K steps in every product
     (5, 8, 1, ("none",)),               # one class: the loss and every gradient are exactly zero
     (9, 1, 5, ("iid", 0.2)),            # hidden size one
+    (1, 4096, 50257, ("none",)),        # a single row against a full-size head: K = 1 in the dW product
+    (3, 2048, 262144 + 7, ("iid", 0.34)),   # three rows, a quarter of a million classes, 1 GB of W in fp32
 ])
 def test_ragged_shapes(dtype, BT, H, V, ignore):
     check_full(workloads.make(BT, H, V, dtype, ignore=ignore, seed=1000 + BT + V, name="ragged"))
