@@ -281,6 +281,16 @@ FLCE_API int flce_get_row_compaction(void);
 FLCE_API int64_t flce_chunk_rows(int64_t BT, int64_t H, int64_t V, int dtype);
 FLCE_API int64_t flce_num_chunks(int64_t BT, int64_t H, int64_t V, int dtype);
 
+/* The largest logits budget (a whole number of 256-row steps, for
+ * flce_set_logits_budget_bytes or flce_options) whose plan for this problem needs at
+ * most max_workspace_bytes of workspace under the current row compaction setting, for
+ * callers who have a fixed amount of memory to give; 0 if not even 256-row chunks
+ * fit (or the arguments are bad).  Fewer rows per chunk cost time: every chunk
+ * re-reads W twice and passes over the fp32 dW partial sums (paper section 3.2, FLCE
+ * paragraph: the chunk size trades memory for speed).  Host only. */
+FLCE_API size_t flce_logits_budget_for_workspace(int64_t BT, int64_t H, int64_t V, int dtype,
+                                                 size_t max_workspace_bytes);
+
 /* Number of K ranges (K = V) the dX product of one chunk is cut into so that its
  * output tiles fill whole rounds of the chip's CUs; 1 = not cut (host only). */
 FLCE_API int flce_dx_k_ranges(int64_t BT, int64_t H, int64_t V, int dtype);

@@ -5,7 +5,7 @@ the argument-marshalling binding with the same names as include/flce.h.
 """
 from .binding import (  # noqa: F401
     FLCE_BF16, FLCE_F32, SKIP_DW, SKIP_DX, FlceError,
-    flce_chunk_rows, flce_cross_entropy_inplace, flce_cross_entropy_inplace_noalloc,
+    flce_chunk_rows, flce_logits_budget_for_workspace, flce_cross_entropy_inplace, flce_cross_entropy_inplace_noalloc,
     CE_NOALLOC_MAX_ROWS, flce_full_logits_bytes, flce_fwd_bwd,
     flce_multihead_fwd_bwd, flce_rmsnorm_fwd_bwd, flce_fwd_bwd_opt, flce_options, flce_workspace_bytes_opt,
     FlceOptions, flce_rmsnorm_workspace_bytes,

@@ -55,6 +55,7 @@ def lib() -> ctypes.CDLL:
             "flce_get_logits_budget_bytes": ([], sz),
             "flce_set_row_compaction": ([ci], ci),
             "flce_get_row_compaction": ([], ci),
+            "flce_logits_budget_for_workspace": ([i64, i64, i64, ci, sz], sz),
             "flce_chunk_rows": ([i64, i64, i64, ci], i64),
             "flce_num_chunks": ([i64, i64, i64, ci], i64),
             "flce_dx_k_ranges": ([i64, i64, i64, ci], ci),
@@ -342,6 +343,10 @@ def flce_set_row_compaction(on: bool):
 
 def flce_get_row_compaction() -> bool:
     return bool(lib().flce_get_row_compaction())
+
+
+def flce_logits_budget_for_workspace(BT, H, V, dtype, max_workspace_bytes) -> int:
+    return int(lib().flce_logits_budget_for_workspace(BT, H, V, _DTYPES.get(dtype, dtype), int(max_workspace_bytes)))
 
 
 def flce_chunk_rows(BT, H, V, dtype) -> int:

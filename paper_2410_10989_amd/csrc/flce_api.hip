@@ -936,6 +936,20 @@ int64_t flce_num_chunks(int64_t BT, int64_t H, int64_t V, int dtype) {
     return plan_for(BT, H, V, dtype).nchunks;
 }
 
+size_t flce_logits_budget_for_workspace(int64_t BT, int64_t H, int64_t V, int dtype, size_t max_workspace_bytes) {
+    if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
+    Settings st = global_settings();
+    const size_t row_bytes = (size_t)round_up(V, 64) * elem_size(dtype);
+    // the workspace grows with the rows per chunk apart from small steps in the dX partial
+    // results, so the first fit from the top is the largest
+    for (int64_t c = round_up(BT, CHUNK_ALIGN); c >= CHUNK_ALIGN; c -= CHUNK_ALIGN) {
+        st.budget = (size_t)c * row_bytes;
+        const Plan p = plan_for(st, BT, H, V, dtype);
+        if (p.total <= max_workspace_bytes && check_launch_limits(p, H, V) == FLCE_OK) return st.budget;
+    }
+    return 0;
+}
+
 int flce_dx_k_ranges(int64_t BT, int64_t H, int64_t V, int dtype) {
     if (check_dims(BT, H, V, dtype) != FLCE_OK) return 0;
     return plan_for(BT, H, V, dtype).dx_ksplit;

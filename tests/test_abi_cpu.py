@@ -201,3 +201,30 @@ def test_options_passed_with_the_call_plan_like_the_setters():
     own.workspace, own.workspace_bytes = a + 2048, need - 1
     assert L.flce_fwd_bwd_opt(a, a + 256, a + 512, 4, 8, 16, -100, 1, a + 768, a + 1024, a + 1280,
                               ctypes.byref(own), None) == 5
+
+
+def test_budget_for_a_workspace_of_a_given_size():
+    code = flce.FLCE_BF16
+    BT, H, V = 131072, 4096, 128256
+    ldz = (V + 63) // 64 * 64
+    old = flce.flce_get_logits_budget_bytes()
+    try:
+        last_rows = None
+        for cap in (1 << 30, 3 << 30, 4 << 30, 8 << 30, 64 << 30):
+            b = flce.flce_logits_budget_for_workspace(BT, H, V, code, cap)
+            if cap == 1 << 30:
+                assert b == 0          # the fp32 dW partial sums alone are 2.1 GB
+                continue
+            assert b > 0 and b % (256 * ldz * 2) == 0
+            flce.flce_set_logits_budget_bytes(b)
+            rows = flce.flce_chunk_rows(BT, H, V, code)
+            assert rows * ldz * 2 <= b or rows == BT      # (chunks are evened out below the budget's row count)
+            assert flce.flce_workspace_bytes(BT, H, V, code) <= cap
+            flce.flce_set_logits_budget_bytes(b + 256 * ldz * 2)      # one step more does not fit
+            assert rows >= BT or flce.flce_workspace_bytes(BT, H, V, code) > cap
+            assert last_rows is None or rows >= last_rows
+            last_rows = rows
+        assert last_rows == BT             # 64 GiB: the whole batch as one chunk
+    finally:
+        flce.flce_set_logits_budget_bytes(old)
+    assert flce.flce_logits_budget_for_workspace(0, H, V, code, 1 << 40) == 0
