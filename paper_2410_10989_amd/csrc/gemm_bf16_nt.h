@@ -72,7 +72,14 @@ constexpr int FG_BM = 256, FG_BN = 256, FG_BK = 64, FG_THREADS = 256;
 constexpr int FG_TILE_BYTES = FG_BM * FG_BK * 2;    // one operand tile of one K step: 32 KB
 constexpr int FG_SLOTS = 5;                         // ring of operand-tile slots
 constexpr int FG_LDS_BYTES = FG_SLOTS * FG_TILE_BYTES;   // 160 KB: the whole LDS of a CU
-constexpr int FG_GROUP_M = 8;
+// Tile rows per group of the tile order (FGArgs::group_m): the 32 tiles an XCD runs at a time are
+// group_m tile rows x 32 / group_m tile columns.  Measured per product at the Llama-3 head (launch
+// times, same box): logits 8: 6.15 ms, 4: 6.20, 16: 6.32, 2: 6.6, 1: 7.7; dX 4 and 8 alike, 6: +1.5 %;
+// dW 8: 6.16 ms, 4: 5.95, 2 and 1: 6.03, 3: 5.97, 16: 6.42.  The dW product's A operand is the
+// chunk of logit gradients read in column form (512-byte pieces 2 ldz bytes apart): the more
+// CUs share such a panel at a time, the better.
+constexpr int FG_GROUP_M_FORWARD = 8;    // logits product
+constexpr int FG_GROUP_M_BACKWARD = 4;   // dX and dW products
 constexpr int FG_XCDS = 8;
 
 struct FGArgs {
@@ -108,6 +115,9 @@ struct FGArgs {
     // 256 to tail_part; fg_tail_reduce_kernel adds them up and writes C.  tail_s <= 1: off.
     int tail_begin, tail_r, tail_s;
     float* tail_part;
+    // Tile order: group_m tile rows at a time, column by column inside such a group (the 32
+    // tiles an XCD runs at a time then share group_m A panels and 32 / group_m B panels).
+    int group_m;
 };
 
 constexpr size_t FG_TAIL_BLOCK_FLOATS = (size_t)FG_BM * FG_BN;   // one fp32 partial block of a tail tile
@@ -460,13 +470,13 @@ __device__ __forceinline__ FgResolved fg_resolve(const FGArgs& a, bool has_in) {
     return r;
 }
 
-// Tile number `seq` of the grouped order (FG_GROUP_M tile rows at a time, column by column
+// Tile number `seq` of the grouped order (group_m tile rows at a time, column by column
 // inside a group) -> first row and column of the tile.
-__device__ __forceinline__ void fg_tile_origin(int seq, int tiles_m, int tiles_n, int& m0, int& n0) {
-    const int group_size = FG_GROUP_M * tiles_n;
+__device__ __forceinline__ void fg_tile_origin(int seq, int tiles_m, int tiles_n, int group_m, int& m0, int& n0) {
+    const int group_size = group_m * tiles_n;
     const int grp = seq / group_size;
-    const int first_m = grp * FG_GROUP_M;
-    const int gm = min(FG_GROUP_M, tiles_m - first_m);
+    const int first_m = grp * group_m;
+    const int gm = min(group_m, tiles_m - first_m);
     const int rem = seq - grp * group_size;
     m0 = (first_m + rem % gm) * FG_BM;
     n0 = (rem / gm) * FG_BN;
@@ -512,7 +522,7 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
     if (in_xcd >= per_xcd || seq_all >= total) return;
     const int split = seq_all / tiles;
     int m0, n0;
-    fg_tile_origin(seq_all - split * tiles, tiles_m, a.tiles_n, m0, n0);
+    fg_tile_origin(seq_all - split * tiles, tiles_m, a.tiles_n, a.group_m, m0, n0);
 
     FgOperand<A_KM> opa;
     FgOperand<B_KM> opb;
@@ -696,7 +706,7 @@ __global__ __launch_bounds__(256) void fg_tail_reduce_kernel(FGArgs a) {
     const int seq = xcd * per_xcd + in_xcd;
     if (in_xcd >= per_xcd || seq >= tiles) return;
     int m0, n0;
-    fg_tile_origin(seq, tiles_m, a.tiles_n, m0, n0);
+    fg_tile_origin(seq, tiles_m, a.tiles_n, a.group_m, m0, n0);
     const float* blk = a.tail_part + (size_t)((xcd * a.tail_r + slot) * a.tail_s) * FG_TAIL_BLOCK_FLOATS;
     const int c4 = ((int)threadIdx.x % 64) * 4;       // first of the thread's 4 columns inside the tile
     const int col = n0 + c4;
