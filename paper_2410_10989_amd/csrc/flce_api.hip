@@ -218,7 +218,7 @@ int launch_gemm_fast(int kind, const bf16_t* A, int64_t lda, const bf16_t* B, in
     FGArgs a{A, lda, B, ldb, C, ldc, Cin, ldcin, (int)M, (int)N, (int)K,
              (int)((M + FG_BM - 1) / FG_BM), (int)((N + FG_BN - 1) / FG_BN), ksplit, split_stride,
              d.rows, d.is_k, d.ksplit, d.first_live, d.launch, 0, 0, 1, tail_part,
-             kind == FLCE_KIND_LOGITS_GEMM ? FG_GROUP_M_FORWARD : FG_GROUP_M_BACKWARD};
+             FG_GROUP_TILES, kind == FLCE_KIND_LOGITS_GEMM ? 1 : 0, 1};
     const int64_t total = (int64_t)a.tiles_m * a.tiles_n * ksplit;
     if (total >= ((int64_t)1 << 30)) return FLCE_ERR_SHAPE;   // the kernel counts tiles in 32 bits
     int64_t wgs_per_xcd = (total + FG_XCDS - 1) / FG_XCDS;

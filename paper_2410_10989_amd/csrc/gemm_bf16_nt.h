@@ -72,14 +72,23 @@ constexpr int FG_BM = 256, FG_BN = 256, FG_BK = 64, FG_THREADS = 256;
 constexpr int FG_TILE_BYTES = FG_BM * FG_BK * 2;    // one operand tile of one K step: 32 KB
 constexpr int FG_SLOTS = 5;                         // ring of operand-tile slots
 constexpr int FG_LDS_BYTES = FG_SLOTS * FG_TILE_BYTES;   // 160 KB: the whole LDS of a CU
-// Tile rows per group of the tile order (FGArgs::group_m): the 32 tiles an XCD runs at a time are
-// group_m tile rows x 32 / group_m tile columns.  Measured per product at the Llama-3 head (launch
-// times, same box): logits 8: 6.15 ms, 4: 6.20, 16: 6.32, 2: 6.6, 1: 7.7; dX 4 and 8 alike, 6: +1.5 %;
-// dW 8: 6.16 ms, 4: 5.95, 2 and 1: 6.03, 3: 5.97, 16: 6.42.  The dW product's A operand is the
-// chunk of logit gradients read in column form (512-byte pieces 2 ldz bytes apart): the more
-// CUs share such a panel at a time, the better.
-constexpr int FG_GROUP_M_FORWARD = 8;    // logits product
-constexpr int FG_GROUP_M_BACKWARD = 4;   // dX and dW products
+// Tile order (FGArgs::group_m, group_cols, xcd_interleave).  The 32 tiles an XCD runs at a time
+// are group_m tile rows x 32 / group_m tile columns (or the other way round), and with
+// xcd_interleave the 8 XCDs run 8 such rounds that follow one another in the order.  What the
+// launches use, measured per product at the Llama-3 and Gemma-2 heads (launch times, one box,
+// other settings as adopted):
+//   logits  groups of 4 tile COLUMNS (4 panels of W, each visited in one stretch, against 8
+//           panels of the chunk's X rows), interleaved: 5.84 ms; groups of 8 tile rows, not
+//           interleaved (the order before): 6.02; 4 columns not interleaved 5.88; 8 columns 5.85;
+//           16 columns 5.99; 2 rows 6.6; 1 row 7.7  (Gemma-2: 5.12 against 5.39 ms)
+//   dX      groups of 4 tile rows, interleaved: 5.88 ms; not interleaved 5.94; 8 rows 5.91 / 5.98;
+//           column groups no better
+//   dW      groups of 4 tile rows, interleaved: 6.04 ms; not interleaved 6.13; 8 rows not
+//           interleaved (the order before) 6.25; 16 rows 6.65; column groups no better
+// The operands that are expensive to fetch (W in the logits product, the chunk of logit
+// gradients read in column form in the dW product: 512-byte pieces 2 ldz bytes apart) want many
+// CUs on the same panel at the same time and few visits of it over the launch.
+constexpr int FG_GROUP_TILES = 4;
 constexpr int FG_XCDS = 8;
 
 struct FGArgs {
@@ -118,6 +127,14 @@ struct FGArgs {
     // Tile order: group_m tile rows at a time, column by column inside such a group (the 32
     // tiles an XCD runs at a time then share group_m A panels and 32 / group_m B panels).
     int group_m;
+    // group_cols = 1: the same order with rows and columns exchanged (groups of group_m tile
+    // COLUMNS, row by row inside a group): every B panel is then visited in one stretch.
+    int group_cols;
+    // xcd_interleave = 1: the full rounds of 32 tiles are dealt to the XCDs round-robin (round j
+    // to XCD j % 8) instead of as one contiguous span per XCD, so that at any time the 8 XCDs
+    // work on 256 consecutive tiles of the order: neighbours that share operand panels beyond
+    // the XCDs' own L2s.  The last, partial round of every XCD is dealt as before.
+    int xcd_interleave;
 };
 
 constexpr size_t FG_TAIL_BLOCK_FLOATS = (size_t)FG_BM * FG_BN;   // one fp32 partial block of a tail tile
@@ -470,16 +487,30 @@ __device__ __forceinline__ FgResolved fg_resolve(const FGArgs& a, bool has_in) {
     return r;
 }
 
+// Position in_xcd of XCD xcd's tile list -> number in the launch's tile sequence (see
+// FGArgs::xcd_interleave).  per_xcd = ceil(total / 8) = 32 F + r.
+__device__ __forceinline__ int fg_seq(const FGArgs& a, int xcd, int in_xcd, int per_xcd) {
+    if (!a.xcd_interleave) return xcd * per_xcd + in_xcd;
+    const int full = per_xcd / TAIL_CUS_PER_XCD * TAIL_CUS_PER_XCD;   // 32 F
+    if (in_xcd < full)
+        return ((in_xcd / TAIL_CUS_PER_XCD) * FG_XCDS + xcd) * TAIL_CUS_PER_XCD + in_xcd % TAIL_CUS_PER_XCD;
+    return full * FG_XCDS + xcd * (per_xcd - full) + (in_xcd - full);
+}
+
 // Tile number `seq` of the grouped order (group_m tile rows at a time, column by column
 // inside a group) -> first row and column of the tile.
-__device__ __forceinline__ void fg_tile_origin(int seq, int tiles_m, int tiles_n, int group_m, int& m0, int& n0) {
-    const int group_size = group_m * tiles_n;
+__device__ __forceinline__ void fg_tile_origin(int seq, int tiles_m, int tiles_n, int group_m, int group_cols,
+                                               int& m0, int& n0) {
+    // (rows and columns change places for the column-grouped order)
+    const int major = group_cols ? tiles_n : tiles_m, minor = group_cols ? tiles_m : tiles_n;
+    const int group_size = group_m * minor;
     const int grp = seq / group_size;
-    const int first_m = grp * group_m;
-    const int gm = min(group_m, tiles_m - first_m);
+    const int first = grp * group_m;
+    const int g = min(group_m, major - first);
     const int rem = seq - grp * group_size;
-    m0 = (first_m + rem % gm) * FG_BM;
-    n0 = (rem / gm) * FG_BN;
+    const int in_major = first + rem % g, in_minor = rem / g;
+    m0 = (group_cols ? in_minor : in_major) * FG_BM;
+    n0 = (group_cols ? in_major : in_minor) * FG_BN;
 }
 
 
@@ -518,11 +549,12 @@ __global__ __launch_bounds__(FG_THREADS) void gemm_bf16_256(FGArgs a) {
         tail_n = a.tail_s;
         tail_blk = (xcd * a.tail_r + slot) * a.tail_s + tail_i;
     }
-    const int seq_all = xcd * per_xcd + in_xcd;
-    if (in_xcd >= per_xcd || seq_all >= total) return;
+    if (in_xcd >= per_xcd) return;
+    const int seq_all = fg_seq(a, xcd, in_xcd, per_xcd);
+    if (seq_all >= total) return;
     const int split = seq_all / tiles;
     int m0, n0;
-    fg_tile_origin(seq_all - split * tiles, tiles_m, a.tiles_n, a.group_m, m0, n0);
+    fg_tile_origin(seq_all - split * tiles, tiles_m, a.tiles_n, a.group_m, a.group_cols, m0, n0);
 
     FgOperand<A_KM> opa;
     FgOperand<B_KM> opb;
@@ -703,10 +735,11 @@ __global__ __launch_bounds__(256) void fg_tail_reduce_kernel(FGArgs a) {
     const int tile_id = (int)blockIdx.x / 8, slab = (int)blockIdx.x % 8;
     const int xcd = tile_id / a.tail_r, slot = tile_id % a.tail_r;
     const int in_xcd = a.tail_begin + slot;
-    const int seq = xcd * per_xcd + in_xcd;
-    if (in_xcd >= per_xcd || seq >= tiles) return;
+    if (in_xcd >= per_xcd) return;
+    const int seq = fg_seq(a, xcd, in_xcd, per_xcd);
+    if (seq >= tiles) return;
     int m0, n0;
-    fg_tile_origin(seq, tiles_m, a.tiles_n, a.group_m, m0, n0);
+    fg_tile_origin(seq, tiles_m, a.tiles_n, a.group_m, a.group_cols, m0, n0);
     const float* blk = a.tail_part + (size_t)((xcd * a.tail_r + slot) * a.tail_s) * FG_TAIL_BLOCK_FLOATS;
     const int c4 = ((int)threadIdx.x % 64) * 4;       // first of the thread's 4 columns inside the tile
     const int col = n0 + c4;
