@@ -488,13 +488,9 @@ __device__ __forceinline__ FgResolved fg_resolve(const FGArgs& a, bool has_in) {
 }
 
 // Position in_xcd of XCD xcd's tile list -> number in the launch's tile sequence (see
-// FGArgs::xcd_interleave).  per_xcd = ceil(total / 8) = 32 F + r.
+// FGArgs::xcd_interleave and xcd_tile_number).
 __device__ __forceinline__ int fg_seq(const FGArgs& a, int xcd, int in_xcd, int per_xcd) {
-    if (!a.xcd_interleave) return xcd * per_xcd + in_xcd;
-    const int full = per_xcd / TAIL_CUS_PER_XCD * TAIL_CUS_PER_XCD;   // 32 F
-    if (in_xcd < full)
-        return ((in_xcd / TAIL_CUS_PER_XCD) * FG_XCDS + xcd) * TAIL_CUS_PER_XCD + in_xcd % TAIL_CUS_PER_XCD;
-    return full * FG_XCDS + xcd * (per_xcd - full) + (in_xcd - full);
+    return a.xcd_interleave ? xcd_tile_number(xcd, in_xcd, per_xcd) : xcd * per_xcd + in_xcd;
 }
 
 // Tile number `seq` of the grouped order (group_m tile rows at a time, column by column

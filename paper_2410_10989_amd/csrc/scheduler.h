@@ -49,6 +49,18 @@ inline TailPlan tail_plan(int64_t total, int64_t ksteps) {
     t.s = s;
     return t;
 }
+// How a launch's tiles, numbered 0 .. total-1 in its tile order, are dealt to the 8 XCDs
+// (workgroup id % 8 is the XCD, id / 8 the position in_xcd in that XCD's list of
+// per_xcd = ceil(total / 8) = 32 F + r tiles): the 8 F full rounds of 32 consecutive numbers
+// go round-robin (round j to XCD j % 8, so that at any time the XCDs work on 256 consecutive
+// tiles), the numbers from 256 F on, at most r per XCD, are dealt in 8 runs of r: these are the
+// tiles tail_plan cuts.  Numbers >= total (the last XCDs' lists can be short) mean "no tile".
+FLCE_HD inline int xcd_tile_number(int xcd, int in_xcd, int per_xcd) {
+    const int full = per_xcd / TAIL_CUS_PER_XCD * TAIL_CUS_PER_XCD;   // 32 F
+    if (in_xcd < full)
+        return ((in_xcd / TAIL_CUS_PER_XCD) * TAIL_XCDS + xcd) * TAIL_CUS_PER_XCD + in_xcd % TAIL_CUS_PER_XCD;
+    return full * TAIL_XCDS + xcd * (per_xcd - full) + (in_xcd - full);
+}
 // bytes of partial blocks such a launch needs (0 when it is not cut)
 inline size_t tail_partial_bytes(int64_t total, int64_t ksteps) {
     const TailPlan t = tail_plan(total, ksteps);

@@ -163,6 +163,31 @@ static void tail_plan_sweep() {
     CHECK(cut > 0, "no launch was cut");
 }
 
+// The deal of a launch's tiles to the XCDs: every tile number below the total comes up exactly
+// once over the 8 lists, the tiles from 256 F on are the last ones of every list (where the cut of
+// the last round expects them), and a full round is 32 consecutive numbers on one XCD.
+static void xcd_deal_sweep() {
+    long checked = 0;
+    for (int total = 1; total <= 70000; total += (total < 1200 ? 1 : 211)) {
+        const int per_xcd = (total + 7) / 8, full = per_xcd / 32 * 32;
+        std::vector<unsigned char> seen((size_t)total, 0);
+        for (int x = 0; x < 8; ++x)
+            for (int i = 0; i < per_xcd; ++i) {
+                const int s = flce::xcd_tile_number(x, i, per_xcd);
+                CHECK(s >= 0, "negative tile number");
+                if (i < full) CHECK(s < 8 * full && s / 32 % 8 == x && s % 32 == i % 32, "round on the wrong XCD");
+                else CHECK(s >= 8 * full, "a leftover tile inside the full rounds");
+                if (s < total) {
+                    CHECK(!seen[(size_t)s], "tile %d dealt twice (total %d)", s, total);
+                    seen[(size_t)s] = 1;
+                }
+                ++checked;
+            }
+        for (int s = 0; s < total; ++s) CHECK(seen[(size_t)s], "tile %d not dealt (total %d)", s, total);
+    }
+    std::printf("xcd deal: %ld positions checked\n", checked);
+}
+
 static void scheduler_sweep() {
     using flce::Plan;
     const int64_t Hs[] = {1, 8, 64, 100, 512, 2304, 3584, 4096, 8192};
@@ -209,6 +234,7 @@ int main() {
     oracle_case(67, 4, 17, 0, true);     // W = 0: loss = log V
     scheduler_sweep();
     tail_plan_sweep();
+    xcd_deal_sweep();
     if (failures) {
         std::printf("%d check(s) failed\n", failures);
         return 1;
